@@ -1,0 +1,173 @@
+/*
+ * bsse.h -- C ABI of libbsse: the batched commitment sweep of a finite Bayesian
+ * Stackelberg game on one AMD MI355X (gfx950).
+ *
+ * Subject.  The paper this library is named after carries the subject only as the
+ * title of a definition box in its preamble ("Alignment Faking: Bayesian-Stackelberg
+ * Equilibria") and states no formula for it; every operation below is therefore
+ * defined by the textbook strong Stackelberg equilibrium of a finite Bayesian game,
+ * restated here:
+ *
+ *   A leader (the overseer) has m actions, a follower (the model) has n actions and
+ *   one of K types t with prior weight prior[t].  A_t[i][j] is the leader's payoff
+ *   and B_t[i][j] the type-t follower's payoff when the leader plays i and the
+ *   follower plays j.  The leader commits to a mixed strategy x (a candidate row of
+ *   m numbers).  A type-t follower answers with
+ *       j*_t(x) = the action maximising  u_t[j] = sum_i x[i]*B_t[i][j];
+ *                 among maximisers, one maximising  l_t[j] = sum_i x[i]*A_t[i][j];
+ *                 among those, the lowest j           (strong-Stackelberg tie-break)
+ *   and the leader's value of x is  V(x) = sum_t prior[t] * l_t[j*_t(x)].
+ *   The sweep evaluates V on every candidate and returns the greatest value, the
+ *   lowest candidate index attaining it, and that candidate's K best responses.
+ *
+ * Arithmetic.  Payoffs are held in fp32 (or bf16, on request) and every sum is
+ * accumulated in fp32; "maximiser" and "equal" mean exact equality of the fp32
+ * numbers the kernel itself computed.  The summation order inside a dot product is
+ * an implementation detail (MFMA paths do not sum in index order).
+ *
+ * Conventions.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device
+ *     memory on the game's device (e.g. torch.Tensor.data_ptr()).
+ *   - Matrices A and B are host, row-major [K][m][n]; they are copied and repacked at
+ *     create and the caller keeps ownership.  Candidates are device, row-major
+ *     [count][m] fp32, borrowed for the duration of the call (until the stream has run
+ *     the enqueued work, for the asynchronous calls).  Rows are NOT checked to lie on
+ *     the simplex: the sweep is defined for any finite x.  Non-finite candidates give
+ *     an unspecified result (never a fault).
+ *   - Every function returns a bsse_status.  Arguments are validated before any HIP
+ *     call, so argument errors are reported on a machine without a GPU.  On error no
+ *     output argument is written.  bsse_last_error() gives a thread-local message.
+ *   - A game handle is not thread-safe; distinct handles are independent.  All device
+ *     work of a handle is enqueued on its stream (default: the null stream).
+ *   - The library never falls back to the CPU: without a usable gfx950 device every
+ *     call that needs one returns BSSE_EDEVICE.
+ */
+#ifndef BSSE_H
+#define BSSE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bsse_game bsse_game; /* opaque: packed payoffs, workspace, running best */
+
+typedef enum {
+    BSSE_OK = 0,
+    BSSE_EINVAL = 1,     /* bad dimension, null pointer, bad option, prior off the simplex */
+    BSSE_ENOTFINITE = 2, /* a payoff or prior entry is NaN or infinite */
+    BSSE_EOVERFLOW = 3,  /* a count does not fit (lattice size, buffer size) */
+    BSSE_ENOMEM = 4,     /* host or device allocation failed */
+    BSSE_EDEVICE = 5,    /* no usable device, or a HIP call failed */
+    BSSE_ESTATE = 6      /* call out of order (e.g. sweep of generated candidates before generating) */
+} bsse_status;
+
+enum { BSSE_STORAGE_F32 = 0, BSSE_STORAGE_BF16 = 1 };
+enum { BSSE_PATH_AUTO = 0, BSSE_PATH_VALU = 1, BSSE_PATH_MFMA = 2 };
+
+typedef struct {
+    int storage; /* BSSE_STORAGE_*: how payoffs (and, for BF16, candidates) enter the
+                    contraction.  BF16 rounds payoffs and each candidate component to
+                    bfloat16 (nearest, ties to even) and accumulates in fp32. */
+    int path;    /* BSSE_PATH_*: AUTO picks MFMA when the shape supports it, else VALU.
+                    MFMA on an unsupported shape is BSSE_EINVAL. */
+    int device;  /* HIP device ordinal; -1 = the calling thread's current device */
+} bsse_options;
+
+typedef struct {
+    double  best_value;   /* V of the winning candidate (the kernel's fp32 value, widened) */
+    int64_t best_index;   /* its index in the swept sequence (index_base + row); -1 if none */
+    int64_t n_evals;      /* candidate-type evaluations accumulated since the last reset */
+    int64_t n_tie_evals;  /* of those, evaluations where two or more follower actions tied
+                             exactly for the maximum (diagnostic) */
+} bsse_result;
+
+/* Problem statement (see top).  m, n, K >= 1; A, B: host [K][m][n]; prior: host [K],
+ * finite, >= 0, |sum - 1| <= 1e-6 (checked, not renormalised).  Limits: m <= 4096,
+ * n <= 65535, K <= 65535, K*m*n <= 2^28.  bsse_create = bsse_create_ex with
+ * {BSSE_STORAGE_F32, BSSE_PATH_AUTO, -1}.  *out is owned by the caller: bsse_destroy. */
+bsse_status bsse_create(int m, int n, int K, const float *A, const float *B,
+                        const float *prior, bsse_game **out);
+bsse_status bsse_create_ex(int m, int n, int K, const float *A, const float *B,
+                           const float *prior, const bsse_options *opt, bsse_game **out);
+void bsse_destroy(bsse_game *g); /* NULL is allowed */
+
+/* Stream (a hipStream_t passed as void*; NULL = null stream) on which all later work
+ * of this handle is enqueued.  The caller keeps the stream alive. */
+bsse_status bsse_set_stream(bsse_game *g, void *hip_stream);
+
+/* Candidate generation, step 1 of the sweep.
+ *
+ * bsse_lattice: generates on the device every point of the simplex lattice of
+ * resolution N (N >= 1): x = k/N for the compositions k of N into m non-negative
+ * parts, in ascending lexicographic order of (k_0..k_{m-1}); each component is
+ * fl32(k_i)/fl32(N), correctly rounded.  The buffer belongs to the handle and replaces
+ * any earlier generated set; *count_out = C(N+m-1, m-1).  BSSE_EOVERFLOW if that count
+ * exceeds 2^40 or the buffer cannot be allocated within device memory.
+ *
+ * bsse_lattice_count: the same count, host only (no device needed).
+ *
+ * bsse_dirichlet: rows first..first+count-1 of the seeded sequence of points uniform
+ * on the simplex (flat Dirichlet): component i of row c is g_i / sum_i g_i with
+ * g_i = -ln(u_i), u_i = ((w_i >> 8) + 1) / 2^24, and w the output words of
+ * Philox4x32-10 keyed by (seed low word, seed high word) at counter
+ * (c low word, c high word, i / 4, 0), word i % 4.  Row c depends on (seed, c) only.
+ * out_dev = device [count][m] fp32 written by the call (asynchronously on the
+ * handle's stream), or NULL to write a handle-owned buffer that replaces any earlier
+ * generated set. */
+bsse_status bsse_lattice(bsse_game *g, int N, int64_t *count_out);
+bsse_status bsse_lattice_count(int m, int N, int64_t *count_out);
+bsse_status bsse_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
+                           float *out_dev);
+
+/* The handle-owned generated set: *dev_out = device pointer ([*count_out][m] fp32),
+ * valid until the next generation call or destroy.  BSSE_ESTATE if none. */
+bsse_status bsse_candidates(bsse_game *g, const float **dev_out, int64_t *count_out);
+
+/* The sweep, steps 2-5 (follower payoffs, tie-broken best responses, leader value,
+ * arg-max over candidates), in one call: resets the running best, sweeps `count` rows
+ * of `candidates_dev` (NULL = the handle-owned generated set, count must then equal
+ * its size or be 0 meaning "all"), waits for the stream, and fills *res and
+ * best_response_out (host, K int32, may be NULL).  count == 0 with explicit candidates
+ * is allowed: best_index = -1 and best_response_out is untouched. */
+bsse_status bsse_sweep(bsse_game *g, const float *candidates_dev, int64_t count,
+                       bsse_result *res, int32_t *best_response_out);
+
+/* The same sweep streamed in chunks (step 6, the running best over chunks):
+ *   bsse_sweep_reset  forgets the running best;
+ *   bsse_sweep_chunk  enqueues the sweep of one chunk whose row r has global index
+ *                     index_base + r, and merges its best into the running best with a
+ *                     strict "greater than", so equal values keep the lowest global
+ *                     index when chunks are submitted in ascending order; it does not
+ *                     wait for the device; the winning row is copied into the handle,
+ *                     so the chunk buffer may be reused once the stream has passed it;
+ *   bsse_sweep_result waits for the stream and reports like bsse_sweep. */
+bsse_status bsse_sweep_reset(bsse_game *g);
+bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t count,
+                             int64_t index_base);
+bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_response_out);
+
+/* Per-candidate outputs of the same kernels (steps 2-4 without the arg-max), for
+ * checking: values_dev_out = device [count] fp32, br_dev_out = device [count][K] int32;
+ * either may be NULL.  Enqueued on the handle's stream; does not wait. */
+bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int64_t count,
+                      float *values_dev_out, int32_t *br_dev_out);
+
+/* Which kernel family the handle uses: "valu", "mfma_f32", "mfma_bf16", ... (static string). */
+const char *bsse_path_name(const bsse_game *g);
+
+/* Kernel timing for roofline reports.  When enabled, every launch of the fused sweep
+ * kernel (payoffs + best response + value + block arg-max) is bracketed by HIP events on
+ * the handle's stream; bsse_get_timing waits for the stream and returns the summed
+ * duration in milliseconds and the number of launches since timing was enabled. */
+bsse_status bsse_set_timing(bsse_game *g, int enabled);
+bsse_status bsse_get_timing(bsse_game *g, double *kernel_ms_out, int64_t *launches_out);
+
+const char *bsse_last_error(void); /* thread-local; "" if none */
+const char *bsse_status_name(bsse_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSSE_H */

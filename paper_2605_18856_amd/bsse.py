@@ -1,0 +1,298 @@
+"""Thin ctypes binding over ``libbsse.so`` -- argument marshalling only.
+
+Function names and argument order are those of ``include/bsse.h``.  Device buffers are
+``torch`` CUDA tensors (PyTorch-ROCm supplies device memory and streams, nothing else);
+every numeric step runs inside the library's HIP kernels.  The library must have been
+built (``python -m paper_2605_18856_amd.build``); there is no fallback of any kind.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbsse.so")
+
+BSSE_OK, BSSE_EINVAL, BSSE_ENOTFINITE, BSSE_EOVERFLOW, BSSE_ENOMEM, BSSE_EDEVICE, BSSE_ESTATE = range(7)
+BSSE_STORAGE_F32, BSSE_STORAGE_BF16 = 0, 1
+BSSE_PATH_AUTO, BSSE_PATH_VALU, BSSE_PATH_MFMA = 0, 1, 2
+
+EXPORTS = [
+    "bsse_create", "bsse_create_ex", "bsse_destroy", "bsse_set_stream", "bsse_lattice",
+    "bsse_lattice_count", "bsse_dirichlet", "bsse_candidates", "bsse_sweep", "bsse_sweep_reset",
+    "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
+    "bsse_get_timing", "bsse_last_error", "bsse_status_name",
+]
+
+
+class bsse_options(ctypes.Structure):
+    _fields_ = [("storage", ctypes.c_int), ("path", ctypes.c_int), ("device", ctypes.c_int)]
+
+
+class bsse_result(ctypes.Structure):
+    _fields_ = [("best_value", ctypes.c_double), ("best_index", ctypes.c_int64),
+                ("n_evals", ctypes.c_int64), ("n_tie_evals", ctypes.c_int64)]
+
+
+class BsseError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{status_name(status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2605_18856_amd.build` "
+                          "(there is no CPU or PyTorch fallback)")
+    try:
+        # PyTorch-ROCm ships its own HIP runtime under the same soname; loading torch first
+        # makes this library bind to that copy, so streams and pointers are shared.
+        import torch  # noqa: F401
+    except ImportError:      # pragma: no cover
+        pass
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
+    P = ctypes.POINTER
+    L.bsse_create.argtypes = [i32, i32, i32, vp, vp, vp, P(vp)]
+    L.bsse_create_ex.argtypes = [i32, i32, i32, vp, vp, vp, P(bsse_options), P(vp)]
+    L.bsse_destroy.argtypes = [vp]
+    L.bsse_destroy.restype = None
+    L.bsse_set_stream.argtypes = [vp, vp]
+    L.bsse_lattice.argtypes = [vp, i32, P(i64)]
+    L.bsse_lattice_count.argtypes = [i32, i32, P(i64)]
+    L.bsse_dirichlet.argtypes = [vp, u64, i64, i64, vp]
+    L.bsse_candidates.argtypes = [vp, P(vp), P(i64)]
+    L.bsse_sweep.argtypes = [vp, vp, i64, P(bsse_result), vp]
+    L.bsse_sweep_reset.argtypes = [vp]
+    L.bsse_sweep_chunk.argtypes = [vp, vp, i64, i64]
+    L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
+    L.bsse_eval.argtypes = [vp, vp, i64, vp, vp]
+    L.bsse_path_name.argtypes = [vp]
+    L.bsse_path_name.restype = ctypes.c_char_p
+    L.bsse_set_timing.argtypes = [vp, i32]
+    L.bsse_get_timing.argtypes = [vp, P(ctypes.c_double), P(i64)]
+    L.bsse_last_error.argtypes = []
+    L.bsse_last_error.restype = ctypes.c_char_p
+    L.bsse_status_name.argtypes = [i32]
+    L.bsse_status_name.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        getattr(L, name)          # AttributeError here means a declared symbol is missing
+    _lib = L
+    return L
+
+
+def status_name(status: int) -> str:
+    return lib().bsse_status_name(int(status)).decode()
+
+
+def bsse_last_error() -> str:
+    return lib().bsse_last_error().decode()
+
+
+def _check(status):
+    if status != BSSE_OK:
+        raise BsseError(status, bsse_last_error())
+
+
+def _host_f32(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None and a.shape != shape:
+        raise ValueError(f"expected shape {shape}, got {a.shape}")
+    return a
+
+
+def _dev_ptr(t, dtype_name, min_elems):
+    """Raw device pointer of a torch CUDA tensor after layout checks (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    want = {"float32": torch.float32, "int32": torch.int32}[dtype_name]
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == want and t.is_contiguous()):
+        raise TypeError(f"expected a contiguous CUDA {dtype_name} tensor")
+    if t.numel() < min_elems:
+        raise ValueError(f"tensor holds {t.numel()} elements, {min_elems} needed")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+@dataclass
+class SweepOutcome:
+    best_value: float
+    best_index: int
+    best_response: Optional[np.ndarray]   # int32[K]; None when nothing was swept
+    n_evals: int
+    n_tie_evals: int
+
+
+class Game:
+    """Owner of one ``bsse_game*`` (released on ``close()`` / garbage collection)."""
+
+    def __init__(self, handle, m, n, K):
+        self._h = handle
+        self.m, self.n, self.K = m, n, K
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise BsseError(BSSE_ESTATE, "game is closed")
+        return self._h
+
+    def close(self):
+        if self._h:
+            lib().bsse_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def bsse_create(m, n, K, A, B, prior, storage=BSSE_STORAGE_F32, path=BSSE_PATH_AUTO,
+                device=-1) -> Game:
+    """A, B: host float32 [K][m][n]; prior: host float32 [K].  Uses the current torch stream."""
+    A = _host_f32(A, (K, m, n))
+    B = _host_f32(B, (K, m, n))
+    prior = _host_f32(prior, (K,))
+    opt = bsse_options(int(storage), int(path), int(device))
+    h = ctypes.c_void_p()
+    _check(lib().bsse_create_ex(m, n, K, A.ctypes.data, B.ctypes.data, prior.ctypes.data,
+                                ctypes.byref(opt), ctypes.byref(h)))
+    g = Game(h, m, n, K)
+    try:
+        import torch
+        if torch.cuda.is_available():
+            bsse_set_stream(g, torch.cuda.current_stream().cuda_stream)
+    except ImportError:      # pragma: no cover
+        pass
+    return g
+
+
+def bsse_destroy(g: Game):
+    g.close()
+
+
+def bsse_set_stream(g: Game, hip_stream: int):
+    _check(lib().bsse_set_stream(g.handle, ctypes.c_void_p(hip_stream)))
+
+
+def bsse_path_name(g: Game) -> str:
+    return lib().bsse_path_name(g.handle).decode()
+
+
+def bsse_lattice_count(m: int, N: int) -> int:
+    c = ctypes.c_int64()
+    _check(lib().bsse_lattice_count(m, N, ctypes.byref(c)))
+    return c.value
+
+
+def bsse_lattice(g: Game, N: int) -> int:
+    c = ctypes.c_int64()
+    _check(lib().bsse_lattice(g.handle, N, ctypes.byref(c)))
+    return c.value
+
+
+def bsse_dirichlet(g: Game, seed: int, first: int, count: int, out=None):
+    """out: CUDA float32 tensor of >= count*m elements, or None for the handle-owned buffer."""
+    _check(lib().bsse_dirichlet(g.handle, ctypes.c_uint64(seed), first, count,
+                                _dev_ptr(out, "float32", count * g.m)))
+
+
+def bsse_candidates(g: Game):
+    """(device pointer, count) of the handle-owned generated set."""
+    p, c = ctypes.c_void_p(), ctypes.c_int64()
+    _check(lib().bsse_candidates(g.handle, ctypes.byref(p), ctypes.byref(c)))
+    return p.value, c.value
+
+
+class _DeviceView:
+    """Zero-copy description of library-owned device memory for torch.as_tensor."""
+
+    def __init__(self, ptr, shape):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": "<f4",
+                                         "data": (int(ptr), False), "version": 2}
+
+
+def candidates_tensor(g: Game):
+    """The handle-owned generated set as a CUDA float32 [count][m] tensor that aliases the
+    library's buffer (valid until the next generation call on this handle)."""
+    import torch
+    ptr, cnt = bsse_candidates(g)
+    if cnt == 0:
+        return torch.empty((0, g.m), dtype=torch.float32, device="cuda")
+    return torch.as_tensor(_DeviceView(ptr, (cnt, g.m)), device="cuda")
+
+
+def candidates_to_host(g: Game) -> np.ndarray:
+    """Copy of the handle-owned generated set as float32 [count][m]."""
+    import torch
+    t = candidates_tensor(g)
+    torch.cuda.current_stream().synchronize()
+    return t.clone().cpu().numpy()
+
+
+def _outcome(g, res, br):
+    has = res.best_index >= 0
+    return SweepOutcome(res.best_value, res.best_index, br.copy() if has else None,
+                        res.n_evals, res.n_tie_evals)
+
+
+def bsse_sweep(g: Game, candidates=None, count: Optional[int] = None) -> SweepOutcome:
+    """candidates: CUDA float32 [count][m] tensor, or None for the generated set."""
+    if candidates is not None and count is None:
+        count = candidates.numel() // g.m
+    if count is None:
+        count = 0
+    res = bsse_result()
+    br = np.full(g.K, -1, dtype=np.int32)
+    _check(lib().bsse_sweep(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                            ctypes.byref(res), br.ctypes.data))
+    return _outcome(g, res, br)
+
+
+def bsse_sweep_reset(g: Game):
+    _check(lib().bsse_sweep_reset(g.handle))
+
+
+def bsse_sweep_chunk(g: Game, candidates, count: int, index_base: int):
+    _check(lib().bsse_sweep_chunk(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                                  index_base))
+
+
+def bsse_sweep_result(g: Game) -> SweepOutcome:
+    res = bsse_result()
+    br = np.full(g.K, -1, dtype=np.int32)
+    _check(lib().bsse_sweep_result(g.handle, ctypes.byref(res), br.ctypes.data))
+    return _outcome(g, res, br)
+
+
+def bsse_eval(g: Game, candidates, count: int, values_out=None, br_out=None):
+    """values_out: CUDA float32 [count]; br_out: CUDA int32 [count][K]; either may be None."""
+    _check(lib().bsse_eval(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                           _dev_ptr(values_out, "float32", count),
+                           _dev_ptr(br_out, "int32", count * g.K)))
+
+
+def bsse_set_timing(g: Game, enabled: bool):
+    _check(lib().bsse_set_timing(g.handle, int(bool(enabled))))
+
+
+def bsse_get_timing(g: Game):
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    _check(lib().bsse_get_timing(g.handle, ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value

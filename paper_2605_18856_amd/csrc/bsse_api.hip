@@ -1,0 +1,598 @@
+// libbsse C ABI: argument checking, payoff packing, device bookkeeping and the chunked sweep
+// driver.  Everything numeric happens in the kernels; nothing here evaluates a payoff.
+#include "../../include/bsse.h"
+#include "bsse_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace bsse;
+
+// ------------------------------------------------------------------------------ errors
+static thread_local char g_err[320] = "";
+
+static bsse_status fail(bsse_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+extern "C" const char *bsse_last_error(void) { return g_err; }
+
+extern "C" const char *bsse_status_name(bsse_status s)
+{
+    switch (s) {
+    case BSSE_OK: return "BSSE_OK";
+    case BSSE_EINVAL: return "BSSE_EINVAL";
+    case BSSE_ENOTFINITE: return "BSSE_ENOTFINITE";
+    case BSSE_EOVERFLOW: return "BSSE_EOVERFLOW";
+    case BSSE_ENOMEM: return "BSSE_ENOMEM";
+    case BSSE_EDEVICE: return "BSSE_EDEVICE";
+    case BSSE_ESTATE: return "BSSE_ESTATE";
+    }
+    return "BSSE_?";
+}
+
+#define HIP_TRY(call)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(e_ == hipErrorOutOfMemory ? BSSE_ENOMEM : BSSE_EDEVICE, "%s: %s",     \
+                        #call, hipGetErrorString(e_));                                        \
+    } while (0)
+
+// ------------------------------------------------------------------------------ handle
+struct HostOut {            // pinned; filled by device-to-host copies in bsse_sweep_result
+    RunningBest run;
+    unsigned long long ties;
+    float fin_v;
+};
+
+struct bsse_game {
+    int m = 0, n = 0, K = 0, storage = 0, device = 0;
+    PathKind path = PATH_VALU;
+    hipStream_t stream = nullptr;
+    GameView view{};
+    // device allocations
+    float *dB = nullptr, *dAT = nullptr, *dprior = nullptr;
+    void *dBpack = nullptr, *dATpack = nullptr;
+    float *gen = nullptr;
+    long long gen_count = -1;
+    size_t gen_cap = 0;
+    unsigned long long *lat_table = nullptr;
+    size_t lat_table_cap = 0;
+    float *blk_v = nullptr;
+    long long *blk_i = nullptr;
+    long long blk_cap = 0;
+    RunningBest *run = nullptr;
+    float *best_x = nullptr;
+    unsigned long long *tie_counter = nullptr;
+    float *fin_v = nullptr;
+    int32_t *fin_br = nullptr;
+    // pinned host
+    HostOut *h_out = nullptr;
+    int32_t *h_br = nullptr;
+    long long n_evals = 0;
+    // kernel timing
+    bool timing = false;
+    std::vector<hipEvent_t> ev;      // start/stop pairs of recorded launches
+    std::vector<hipEvent_t> ev_pool; // recycled events
+    double timed_ms = 0.0;
+    long long timed_launches = 0;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+float host_round_bf16(float v)
+{
+    uint32_t b;
+    memcpy(&b, &v, 4);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    b &= 0xFFFF0000u;
+    memcpy(&v, &b, 4);
+    return v;
+}
+
+// C(N+m-1, m-1) with overflow detection; returns false when it exceeds `cap`.
+bool lattice_count_checked(int m, int N, unsigned long long cap, unsigned long long *out)
+{
+    unsigned long long k = (unsigned long long)(m - 1), a = (unsigned long long)N + k;
+    if (k > (unsigned long long)N) k = (unsigned long long)N;       // C(a,k) = C(a,a-k)
+    unsigned __int128 c = 1;
+    for (unsigned long long i = 1; i <= k; ++i) {
+        c = c * (a - k + i) / i;             // exact: a product of i consecutive integers / i!
+        if (c > (unsigned __int128)cap) return false;
+    }
+    *out = (unsigned long long)c;
+    return true;
+}
+
+constexpr unsigned long long LATTICE_MAX = 1ull << 40;
+constexpr long long CHUNK_MAX = 1ll << 31;
+
+void free_game(bsse_game *g)
+{
+    if (!g) return;
+    DeviceGuard dg(g->device);
+    (void)hipFree(g->dB); (void)hipFree(g->dAT); (void)hipFree(g->dprior);
+    (void)hipFree(g->dBpack); (void)hipFree(g->dATpack);
+    (void)hipFree(g->gen); (void)hipFree(g->lat_table);
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
+    (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
+    (void)hipFree(g->fin_v); (void)hipFree(g->fin_br);
+    if (g->h_out) (void)hipHostFree(g->h_out);
+    if (g->h_br) (void)hipHostFree(g->h_br);
+    for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g->ev_pool) (void)hipEventDestroy(e);
+    delete g;
+}
+
+bsse_status ensure_blocks(bsse_game *g, long long nblocks)
+{
+    if (nblocks <= g->blk_cap) return BSSE_OK;
+    // the stream may still be reading the old workspace
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
+    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_cap = 0;
+    HIP_TRY(hipMalloc((void **)&g->blk_v, (size_t)nblocks * sizeof(float)));
+    HIP_TRY(hipMalloc((void **)&g->blk_i, (size_t)nblocks * sizeof(long long)));
+    g->blk_cap = nblocks;
+    return BSSE_OK;
+}
+
+bsse_status ensure_gen(bsse_game *g, unsigned long long rows)
+{
+    const unsigned long long bytes = rows * (unsigned long long)g->m * sizeof(float);
+    if (bytes <= g->gen_cap) return BSSE_OK;
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    (void)hipFree(g->gen);
+    g->gen = nullptr; g->gen_cap = 0; g->gen_count = -1;
+    size_t free_b = 0, total_b = 0;
+    HIP_TRY(hipMemGetInfo(&free_b, &total_b));
+    if (bytes > free_b)
+        return fail(BSSE_EOVERFLOW, "candidate buffer of %llu bytes exceeds free device memory (%zu)",
+                    bytes, free_b);
+    HIP_TRY(hipMalloc((void **)&g->gen, (size_t)bytes));
+    g->gen_cap = (size_t)bytes;
+    return BSSE_OK;
+}
+
+hipError_t launch_sweep(bsse_game *g, const SweepArgs &a, bool eval)
+{
+    if (g->path == PATH_VALU) return launch_sweep_valu(g->view, a, eval, g->stream);
+    return launch_sweep_mfma(g->view, g->path, a, eval, g->stream);
+}
+
+long long sweep_blocks(const bsse_game *g, long long count)
+{
+    return g->path == PATH_VALU ? valu_num_blocks(count) : mfma_num_blocks(g->view, g->path, count);
+}
+
+bsse_status take_event(bsse_game *g, hipEvent_t *e)
+{
+    if (!g->ev_pool.empty()) { *e = g->ev_pool.back(); g->ev_pool.pop_back(); return BSSE_OK; }
+    HIP_TRY(hipEventCreate(e));
+    return BSSE_OK;
+}
+
+bsse_status drain_timing(bsse_game *g)
+{
+    for (size_t i = 0; i + 1 < g->ev.size(); i += 2) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, g->ev[i], g->ev[i + 1]));
+        g->timed_ms += ms;
+        g->timed_launches += 1;
+    }
+    for (hipEvent_t e : g->ev) g->ev_pool.push_back(e);
+    g->ev.clear();
+    return BSSE_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------ create
+extern "C" bsse_status bsse_create(int m, int n, int K, const float *A, const float *B,
+                                   const float *prior, bsse_game **out)
+{
+    bsse_options opt = { BSSE_STORAGE_F32, BSSE_PATH_AUTO, -1 };
+    return bsse_create_ex(m, n, K, A, B, prior, &opt, out);
+}
+
+extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const float *B,
+                                      const float *prior, const bsse_options *opt,
+                                      bsse_game **out)
+{
+    g_err[0] = 0;
+    if (!out) return fail(BSSE_EINVAL, "out is NULL");
+    if (!A || !B || !prior) return fail(BSSE_EINVAL, "A, B and prior must not be NULL");
+    if (!opt) return fail(BSSE_EINVAL, "opt is NULL");
+    if (m < 1 || n < 1 || K < 1) return fail(BSSE_EINVAL, "m, n, K must be >= 1 (got %d, %d, %d)", m, n, K);
+    if (m > 4096 || n > 65535 || K > 65535)
+        return fail(BSSE_EINVAL, "limits: m <= 4096, n <= 65535, K <= 65535 (got %d, %d, %d)", m, n, K);
+    const unsigned long long elems = (unsigned long long)m * n * K;
+    if (elems > (1ull << 28)) return fail(BSSE_EINVAL, "K*m*n = %llu exceeds 2^28", elems);
+    if (opt->storage != BSSE_STORAGE_F32 && opt->storage != BSSE_STORAGE_BF16)
+        return fail(BSSE_EINVAL, "unknown storage option %d", opt->storage);
+    if (opt->path != BSSE_PATH_AUTO && opt->path != BSSE_PATH_VALU && opt->path != BSSE_PATH_MFMA)
+        return fail(BSSE_EINVAL, "unknown path option %d", opt->path);
+    if (opt->device < -1) return fail(BSSE_EINVAL, "bad device ordinal %d", opt->device);
+    for (unsigned long long e = 0; e < elems; ++e)
+        if (!std::isfinite(A[e]) || !std::isfinite(B[e]))
+            return fail(BSSE_ENOTFINITE, "payoff entry %llu is not finite", e);
+    double psum = 0.0;
+    for (int t = 0; t < K; ++t) {
+        if (!std::isfinite(prior[t])) return fail(BSSE_ENOTFINITE, "prior[%d] is not finite", t);
+        if (prior[t] < 0.0f) return fail(BSSE_EINVAL, "prior[%d] is negative", t);
+        psum += (double)prior[t];
+    }
+    if (std::fabs(psum - 1.0) > 1e-6) return fail(BSSE_EINVAL, "prior sums to %.9g, not 1", psum);
+    const bool can_mfma = mfma_supported(m, n, K, opt->storage);
+    if (opt->path == BSSE_PATH_MFMA && !can_mfma)
+        return fail(BSSE_EINVAL, "shape m=%d n=%d K=%d has no MFMA path", m, n, K);
+
+    // ---- device
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1)
+        return fail(BSSE_EDEVICE, "no HIP device is visible");
+    int dev = opt->device;
+    if (dev < 0 && hipGetDevice(&dev) != hipSuccess) return fail(BSSE_EDEVICE, "hipGetDevice failed");
+    if (dev >= ndev) return fail(BSSE_EINVAL, "device %d of %d does not exist", dev, ndev);
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(BSSE_EDEVICE, "device %d is %s; this library holds gfx950 code only", dev,
+                    prop.gcnArchName);
+
+    bsse_game *g = new (std::nothrow) bsse_game;
+    if (!g) return fail(BSSE_ENOMEM, "host allocation failed");
+    g->m = m; g->n = n; g->K = K; g->storage = opt->storage; g->device = dev;
+    const bool use_mfma = can_mfma && opt->path != BSSE_PATH_VALU;
+    g->path = !use_mfma ? PATH_VALU
+              : (opt->storage == BSSE_STORAGE_BF16 ? PATH_MFMA_BF16 : PATH_MFMA_F32);
+
+    DeviceGuard dg(dev);
+    if (!dg.ok) { free_game(g); return fail(BSSE_EDEVICE, "hipSetDevice(%d) failed", dev); }
+
+    // ---- pack on the host: optional bf16 rounding, B as given, A transposed per type
+    std::vector<float> hB(elems), hAT(elems), hA;
+    const bool bf = opt->storage == BSSE_STORAGE_BF16;
+    for (unsigned long long e = 0; e < elems; ++e) hB[e] = bf ? host_round_bf16(B[e]) : B[e];
+    for (int t = 0; t < K; ++t)
+        for (int i = 0; i < m; ++i)
+            for (int j = 0; j < n; ++j) {
+                const float a = A[((size_t)t * m + i) * n + j];
+                hAT[((size_t)t * n + j) * m + i] = bf ? host_round_bf16(a) : a;
+            }
+
+    bsse_status st = BSSE_OK;
+    auto up = [&](void **dst, const void *src, size_t bytes) -> bsse_status {
+        HIP_TRY(hipMalloc(dst, bytes));
+        HIP_TRY(hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice));
+        return BSSE_OK;
+    };
+    auto zeroed = [&](void **dst, size_t bytes) -> bsse_status {
+        HIP_TRY(hipMalloc(dst, bytes));
+        HIP_TRY(hipMemset(*dst, 0, bytes));
+        return BSSE_OK;
+    };
+    do {
+        if ((st = up((void **)&g->dB, hB.data(), elems * 4)) != BSSE_OK) break;
+        if ((st = up((void **)&g->dAT, hAT.data(), elems * 4)) != BSSE_OK) break;
+        if ((st = up((void **)&g->dprior, prior, (size_t)K * 4)) != BSSE_OK) break;
+        g->view.m_pad = m; g->view.n_pad = n;
+        if (use_mfma) {
+            void *pb = nullptr, *pa = nullptr;
+            size_t bb = 0, ab = 0;
+            mfma_pack(m, n, K, opt->storage, A, B, &pb, &bb, &pa, &ab, &g->view.m_pad, &g->view.n_pad);
+            if (!pb || !pa) { free(pb); free(pa); st = fail(BSSE_ENOMEM, "host allocation failed"); break; }
+            st = up(&g->dBpack, pb, bb);
+            if (st == BSSE_OK) st = up(&g->dATpack, pa, ab);
+            free(pb); free(pa);
+            if (st != BSSE_OK) break;
+        }
+        if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->fin_v, 4)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->fin_br, (size_t)K * 4)) != BSSE_OK) break;
+        hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
+        if (e != hipSuccess) { st = fail(BSSE_ENOMEM, "hipHostMalloc: %s", hipGetErrorString(e)); break; }
+    } while (0);
+    if (st != BSSE_OK) { free_game(g); return st; }
+
+    g->view.m = m; g->view.n = n; g->view.K = K;
+    g->view.x_bf16 = bf ? 1 : 0;
+    g->view.B = g->dB; g->view.AT = g->dAT; g->view.prior = g->dprior;
+    g->view.Bpack = g->dBpack; g->view.ATpack = g->dATpack;
+    *out = g;
+    return BSSE_OK;
+}
+
+extern "C" void bsse_destroy(bsse_game *g)
+{
+    if (!g) return;
+    {
+        DeviceGuard dg(g->device);
+        (void)hipStreamSynchronize(g->stream);
+    }
+    free_game(g);
+}
+
+extern "C" bsse_status bsse_set_stream(bsse_game *g, void *hip_stream)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    DeviceGuard dg(g->device);
+    HIP_TRY(hipStreamSynchronize(g->stream));     // earlier work keeps its order
+    g->stream = (hipStream_t)hip_stream;
+    return BSSE_OK;
+}
+
+extern "C" const char *bsse_path_name(const bsse_game *g)
+{
+    if (!g) return "";
+    switch (g->path) {
+    case PATH_VALU: return g->storage == BSSE_STORAGE_BF16 ? "valu_bf16" : "valu";
+    case PATH_MFMA_F32: return "mfma_f32";
+    case PATH_MFMA_BF16: return "mfma_bf16";
+    }
+    return "";
+}
+
+// --------------------------------------------------------------------------- generation
+extern "C" bsse_status bsse_lattice_count(int m, int N, int64_t *count_out)
+{
+    g_err[0] = 0;
+    if (!count_out) return fail(BSSE_EINVAL, "count_out is NULL");
+    if (m < 1 || m > 4096) return fail(BSSE_EINVAL, "m must be in 1..4096 (got %d)", m);
+    if (N < 1 || N > (1 << 24)) return fail(BSSE_EINVAL, "N must be in 1..2^24 (got %d)", N);
+    unsigned long long c = 0;
+    if (!lattice_count_checked(m, N, LATTICE_MAX, &c))
+        return fail(BSSE_EOVERFLOW, "lattice of resolution %d in %d parts has more than 2^40 points", N, m);
+    *count_out = (int64_t)c;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_lattice(bsse_game *g, int N, int64_t *count_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!count_out) return fail(BSSE_EINVAL, "count_out is NULL");
+    int64_t cnt = 0;
+    bsse_status st = bsse_lattice_count(g->m, N, &cnt);
+    if (st != BSSE_OK) return st;
+    const int m = g->m;
+    // W(R,q) = C(R+q-1, q-1) for q = 0..m, R = 0..N by Pascal's rule; every entry <= cnt
+    const size_t tab_elems = (size_t)(m + 1) * (N + 1);
+    if (tab_elems > (1ull << 27)) return fail(BSSE_EOVERFLOW, "lattice table of %zu entries is too large", tab_elems);
+    std::vector<unsigned long long> tab(tab_elems, 0ull);
+    for (int q = 1; q <= m; ++q)
+        for (int R = 0; R <= N; ++R) {
+            unsigned long long v;
+            if (q == 1 || R == 0) v = 1;
+            else v = tab[(size_t)q * (N + 1) + R - 1] + tab[(size_t)(q - 1) * (N + 1) + R];
+            tab[(size_t)q * (N + 1) + R] = v;
+        }
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    if ((st = ensure_gen(g, (unsigned long long)cnt)) != BSSE_OK) return st;
+    if (tab_elems * 8 > g->lat_table_cap) {
+        HIP_TRY(hipStreamSynchronize(g->stream));
+        (void)hipFree(g->lat_table);
+        g->lat_table = nullptr; g->lat_table_cap = 0;
+        HIP_TRY(hipMalloc((void **)&g->lat_table, tab_elems * 8));
+        g->lat_table_cap = tab_elems * 8;
+    }
+    HIP_TRY(hipMemcpyAsync(g->lat_table, tab.data(), tab_elems * 8, hipMemcpyHostToDevice, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));     // `tab` is pageable and dies with this frame
+    HIP_TRY(launch_lattice(g->lat_table, m, N, cnt, g->gen, g->stream));
+    g->gen_count = cnt;
+    *count_out = cnt;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
+                                      float *out_dev)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (first < 0 || count < 0) return fail(BSSE_EINVAL, "first and count must be >= 0");
+    if (count > CHUNK_MAX) return fail(BSSE_EOVERFLOW, "count exceeds 2^31 rows per call");
+    if (first > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "first + count overflows");
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    float *dst = out_dev;
+    if (!dst) {
+        bsse_status st = ensure_gen(g, (unsigned long long)count);
+        if (st != BSSE_OK) return st;
+        dst = g->gen;
+    }
+    HIP_TRY(launch_dirichlet(seed, first, count, g->m, dst, g->stream));
+    if (!out_dev) g->gen_count = count;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_candidates(bsse_game *g, const float **dev_out, int64_t *count_out)
+{
+    g_err[0] = 0;
+    if (!g || !dev_out || !count_out) return fail(BSSE_EINVAL, "NULL argument");
+    if (g->gen_count < 0) return fail(BSSE_ESTATE, "no candidate set has been generated on this handle");
+    *dev_out = g->gen;
+    *count_out = g->gen_count;
+    return BSSE_OK;
+}
+
+// -------------------------------------------------------------------------------- sweep
+extern "C" bsse_status bsse_sweep_reset(bsse_game *g)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    HIP_TRY(launch_reset(g->run, g->tie_counter, g->stream));
+    g->n_evals = 0;
+    return BSSE_OK;
+}
+
+static bsse_status resolve_candidates(bsse_game *g, const float **X, int64_t *count)
+{
+    if (*count < 0) return fail(BSSE_EINVAL, "count must be >= 0");
+    if (!*X) {
+        if (g->gen_count < 0)
+            return fail(BSSE_ESTATE, "candidates is NULL but no set has been generated on this handle");
+        if (*count != 0 && *count != g->gen_count)
+            return fail(BSSE_EINVAL, "count %lld does not match the generated set (%lld)",
+                        (long long)*count, g->gen_count);
+        *X = g->gen;
+        *count = g->gen_count;
+    }
+    if (*count > CHUNK_MAX) return fail(BSSE_EOVERFLOW, "count exceeds 2^31 rows per call");
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t count,
+                                        int64_t index_base)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (index_base < 0) return fail(BSSE_EINVAL, "index_base must be >= 0");
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    if (index_base > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "index_base + count overflows");
+    if (count == 0) return BSSE_OK;
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    const long long nblocks = sweep_blocks(g, count);
+    if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
+    SweepArgs a{};
+    a.X = candidates_dev; a.count = count; a.index_base = index_base;
+    a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (g->timing) {
+        if ((st = take_event(g, &e0)) != BSSE_OK) return st;
+        if ((st = take_event(g, &e1)) != BSSE_OK) { g->ev_pool.push_back(e0); return st; }
+        HIP_TRY(hipEventRecord(e0, g->stream));
+    }
+    hipError_t le = launch_sweep(g, a, false);
+    if (g->timing) {
+        (void)hipEventRecord(e1, g->stream);
+        g->ev.push_back(e0); g->ev.push_back(e1);
+    }
+    HIP_TRY(le);
+    HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, candidates_dev, index_base, g->m,
+                                g->run, g->best_x, g->stream));
+    g->n_evals += (long long)count * g->K;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!res) return fail(BSSE_EINVAL, "res is NULL");
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    // best responses of the winner: the same kernel, one row, per-candidate outputs on
+    SweepArgs a{};
+    a.X = g->best_x; a.count = 1; a.index_base = 0;
+    a.V_out = g->fin_v; a.br_out = g->fin_br;
+    HIP_TRY(launch_sweep(g, a, true));
+    HIP_TRY(hipMemcpyAsync(&g->h_out->run, g->run, sizeof(RunningBest), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(&g->h_out->ties, g->tie_counter, 8, hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(&g->h_out->fin_v, g->fin_v, 4, hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(g->h_br, g->fin_br, (size_t)g->K * 4, hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    const bool has = g->h_out->run.has != 0;
+    if (has && !(g->h_out->fin_v == g->h_out->run.value))
+        return fail(BSSE_EDEVICE, "internal: re-evaluated winner value %.9g differs from swept value %.9g",
+                    (double)g->h_out->fin_v, (double)g->h_out->run.value);
+    res->best_value = has ? (double)g->h_out->run.value : 0.0;
+    res->best_index = has ? (int64_t)g->h_out->run.index : -1;
+    res->n_evals = g->n_evals;
+    res->n_tie_evals = (int64_t)g->h_out->ties;
+    if (has && best_response_out) memcpy(best_response_out, g->h_br, (size_t)g->K * 4);
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_sweep(bsse_game *g, const float *candidates_dev, int64_t count,
+                                  bsse_result *res, int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!res) return fail(BSSE_EINVAL, "res is NULL");
+    {   // argument errors first, before anything is enqueued
+        const float *x = candidates_dev;
+        int64_t c = count;
+        bsse_status st = resolve_candidates(g, &x, &c);
+        if (st != BSSE_OK) return st;
+    }
+    bsse_status st = bsse_sweep_reset(g);
+    if (st != BSSE_OK) return st;
+    if ((st = bsse_sweep_chunk(g, candidates_dev, count, 0)) != BSSE_OK) return st;
+    return bsse_sweep_result(g, res, best_response_out);
+}
+
+extern "C" bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int64_t count,
+                                 float *values_dev_out, int32_t *br_dev_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    if (count == 0 || (!values_dev_out && !br_dev_out)) return BSSE_OK;
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    SweepArgs a{};
+    a.X = candidates_dev; a.count = count; a.index_base = 0;
+    a.V_out = values_dev_out; a.br_out = br_dev_out;
+    HIP_TRY(launch_sweep(g, a, true));
+    return BSSE_OK;
+}
+
+// ------------------------------------------------------------------------------- timing
+extern "C" bsse_status bsse_set_timing(bsse_game *g, int enabled)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    DeviceGuard dg(g->device);
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    for (hipEvent_t e : g->ev) g->ev_pool.push_back(e);
+    g->ev.clear();
+    g->timed_ms = 0.0; g->timed_launches = 0;
+    g->timing = enabled != 0;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_get_timing(bsse_game *g, double *kernel_ms_out, int64_t *launches_out)
+{
+    g_err[0] = 0;
+    if (!g || !kernel_ms_out || !launches_out) return fail(BSSE_EINVAL, "NULL argument");
+    DeviceGuard dg(g->device);
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    bsse_status st = drain_timing(g);
+    if (st != BSSE_OK) return st;
+    *kernel_ms_out = g->timed_ms;
+    *launches_out = g->timed_launches;
+    return BSSE_OK;
+}

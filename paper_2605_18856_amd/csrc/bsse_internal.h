@@ -1,0 +1,70 @@
+// Internal declarations shared by the translation units of libbsse (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bsse {
+
+// Device view of one game, passed to kernels by value.  All pointers are device memory
+// owned by the handle.
+struct GameView {
+    int m, n, K;
+    int x_bf16;           // 1: round each candidate component to bf16 before use
+    const float *B;       // [K][m][n]  follower payoffs, row-major (VALU path)
+    const float *AT;      // [K][n][m]  leader payoffs, one follower action's column contiguous
+    const float *prior;   // [K]
+    // MFMA paths (null when the shape has no MFMA packing)
+    const void *Bpack;    // follower payoffs in MFMA A-operand fragment order
+    const void *ATpack;   // leader payoffs [K][n][m_pad] in the contraction's k order
+    int m_pad;            // m rounded up to the MFMA k granularity
+    int n_pad;            // n rounded up to the row-tile granularity (see sweep_mfma.hip)
+};
+
+// One sweep launch.  Either (V_out, br_out) [evaluation mode: per-candidate outputs] or
+// (blk_v, blk_i) [sweep mode: one record per workgroup] is used.
+struct SweepArgs {
+    const float *X;          // [count][m] fp32
+    long long count;
+    long long index_base;    // global index of row 0
+    float *V_out;            // [count]            (evaluation mode, nullable)
+    int32_t *br_out;         // [count][K]         (evaluation mode, nullable)
+    float *blk_v;            // [nblocks]          (sweep mode)
+    long long *blk_i;        // [nblocks] global candidate index, LLONG_MAX if none
+    unsigned long long *tie_counter;  // += number of (candidate,type) evaluations with a tie
+};
+
+// Running best over chunks, in device memory.
+struct RunningBest {
+    float value;
+    int   has;               // 0 until a chunk has been merged
+    long long index;
+};
+
+enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3 };
+
+// --- launchers (each validates nothing: the API layer has checked shapes) ----------------
+// Number of workgroup records the sweep-mode launch of `count` candidates writes.
+long long valu_num_blocks(long long count);
+hipError_t launch_sweep_valu(const GameView &g, const SweepArgs &a, bool eval, hipStream_t s);
+
+bool mfma_supported(int m, int n, int K, int storage);
+long long mfma_num_blocks(const GameView &g, PathKind kind, long long count);
+hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &a, bool eval,
+                             hipStream_t s);
+// Host-side packing of payoffs for the MFMA paths; returns malloc'ed buffers (caller frees).
+void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
+               void **Bpack, size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad,
+               int *n_pad);
+
+hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
+                               const float *X, long long index_base, int m, RunningBest *run,
+                               float *best_x, hipStream_t s);
+
+hipError_t launch_reset(RunningBest *run, unsigned long long *tie_counter, hipStream_t s);
+
+hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
+                          float *out, hipStream_t s);
+hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m, float *out,
+                            hipStream_t s);
+
+}  // namespace bsse

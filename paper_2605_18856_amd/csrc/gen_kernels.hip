@@ -1,0 +1,173 @@
+// Candidate generation on the device (step 1 of the sweep): simplex-lattice unranking and
+// seeded flat-Dirichlet rows.  Both kernels are write-bound: one coalesced pass over the
+// output, no reads beyond a small table.
+#include "bsse_internal.h"
+
+namespace bsse {
+
+// ---------------------------------------------------------------------------------------
+// Lattice.  Points are the compositions k of N into m parts in ascending lexicographic
+// order.  table[q*(N+1) + R] = W(R, q) = C(R+q-1, q-1), the number of compositions of R
+// into q parts (q = 1..m, R = 0..N).  With `rem` left to distribute over this part and q
+// later parts, the compositions whose current part is < v number
+//     S(v) = sum_{v'<v} W(rem-v', q) = W(rem, q+1) - W(rem-v, q+1)
+// (hockey-stick identity), which is increasing in v, so the part is the largest v with
+// S(v) <= rank, found by bisection.
+__global__ void __launch_bounds__(256)
+lattice_kernel(const unsigned long long *__restrict__ table, int m, int N, long long count,
+               float *__restrict__ out)
+{
+    const float fN = (float)N;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < count; r += stride) {
+        unsigned long long rr = (unsigned long long)r;
+        int rem = N;
+        float *row = out + r * m;
+        for (int i = 0; i < m - 1; ++i) {
+            const int q = m - 1 - i;
+            const unsigned long long *Wq1 = table + (size_t)(q + 1) * (N + 1);
+            const unsigned long long top = Wq1[rem];
+            int lo = 0, hi = rem;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (top - Wq1[rem - mid] <= rr) lo = mid; else hi = mid - 1;
+            }
+            rr -= top - Wq1[rem - lo];
+            rem -= lo;
+            row[i] = (float)lo / fN;       // IEEE division (correctly rounded)
+        }
+        row[m - 1] = (float)rem / fN;
+    }
+}
+
+hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
+                          float *out, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    long long blocks = (count + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(lattice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, table, m, N, count,
+                       out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Philox4x32 with 10 rounds, from the description in Salmon, Moraes, Dror, Shaw (SC'11):
+// two 32x32->64 multiplies per round feed a fixed permutation with key injection; the key
+// advances by two Weyl constants between rounds.
+struct U4 { unsigned x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(U4 c, unsigned k0, unsigned k1)
+{
+#pragma unroll
+    for (int rnd = 0; rnd < 10; ++rnd) {
+        const unsigned hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+        const unsigned hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        U4 d;
+        d.x = hi1 ^ c.y ^ k0;
+        d.y = lo1;
+        d.z = hi0 ^ c.w ^ k1;
+        d.w = lo0;
+        c = d;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c;
+}
+
+// A 32-bit word to a unit exponential: u = ((w >> 8) + 1) / 2^24 is in (0, 1].
+__device__ __forceinline__ float unit_exponential(unsigned w)
+{
+    const float u = (float)((w >> 8) + 1u) * 5.9604644775390625e-08f;   // exact: < 2^24+1
+    return -logf(u);
+}
+
+// One thread per (row, group of four components): one Philox call, one float4 store, so a
+// wavefront writes 1 KiB contiguously.  Requires m % 4 == 0 and m/4 a power of two <= 64, so
+// that a row's threads sit in one wavefront and the row sum is a butterfly over them.
+__global__ void __launch_bounds__(256)
+dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count, int m,
+                      int log2_nb, float *__restrict__ out)
+{
+    const int nb = 1 << log2_nb;
+    const long long quads = count << log2_nb;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    const long long q0 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    // all lanes of a wavefront iterate together (quads and stride are multiples of nb and the
+    // trip count is uniform per row group), so the shuffles below see every partner lane
+    for (long long base = q0 - threadIdx.x % 64; base < quads; base += stride) {
+        const long long q = base + threadIdx.x % 64;
+        const bool live = q < quads;
+        const long long row = first + (q >> log2_nb);
+        const unsigned b = (unsigned)(q & (nb - 1));
+        U4 c = { (unsigned)(unsigned long long)row, (unsigned)((unsigned long long)row >> 32), b, 0u };
+        const U4 w = philox4x32_10(c, k0, k1);
+        float g0 = unit_exponential(w.x), g1 = unit_exponential(w.y);
+        float g2 = unit_exponential(w.z), g3 = unit_exponential(w.w);
+        float sum = (g0 + g1) + (g2 + g3);
+        for (int d = 1; d < nb; d <<= 1) sum += __shfl_xor(sum, d, 64);
+        float4 v;
+        if (sum > 0.0f) {
+            v = make_float4(g0 / sum, g1 / sum, g2 / sum, g3 / sum);
+        } else {
+            const float e = 1.0f / (float)m;
+            v = make_float4(e, e, e, e);
+        }
+        if (live) reinterpret_cast<float4 *>(out)[q] = v;
+    }
+}
+
+// Any m: one thread per row, two passes over the generator (sum, then normalise).
+__global__ void __launch_bounds__(256)
+dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count, int m,
+                     float *__restrict__ out)
+{
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < count; r += stride) {
+        const long long row = first + r;
+        const unsigned c0 = (unsigned)(unsigned long long)row;
+        const unsigned c1 = (unsigned)((unsigned long long)row >> 32);
+        const int nb = (m + 3) / 4;
+        float sum = 0.0f;
+        for (int b = 0; b < nb; ++b) {
+            const U4 w = philox4x32_10(U4{ c0, c1, (unsigned)b, 0u }, k0, k1);
+            const unsigned ww[4] = { w.x, w.y, w.z, w.w };
+            for (int e = 0; e < 4; ++e)
+                if (4 * b + e < m) sum += unit_exponential(ww[e]);
+        }
+        for (int b = 0; b < nb; ++b) {
+            const U4 w = philox4x32_10(U4{ c0, c1, (unsigned)b, 0u }, k0, k1);
+            const unsigned ww[4] = { w.x, w.y, w.z, w.w };
+            for (int e = 0; e < 4; ++e)
+                if (4 * b + e < m)
+                    out[r * m + 4 * b + e] =
+                        sum > 0.0f ? unit_exponential(ww[e]) / sum : 1.0f / (float)m;
+        }
+    }
+}
+
+hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m, float *out,
+                            hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    const unsigned k0 = (unsigned)(seed & 0xFFFFFFFFull), k1 = (unsigned)(seed >> 32);
+    int nb = m / 4, log2_nb = 0;
+    while ((1 << log2_nb) < nb) ++log2_nb;
+    const bool quad_ok = (m % 4 == 0) && nb >= 1 && (1 << log2_nb) == nb && nb <= 64 &&
+                         ((uintptr_t)out % 16 == 0);
+    if (quad_ok) {
+        const long long quads = count * nb;
+        long long blocks = (quads + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(dirichlet_quad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
+                           first, count, m, log2_nb, out);
+    } else {
+        long long blocks = (count + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(dirichlet_row_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
+                           first, count, m, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace bsse

@@ -1,0 +1,92 @@
+// Step 5/6: grid stage of the arg-max over candidates, and the merge into the running best
+// over chunks.  The sweep kernels leave one (value, global index) record per workgroup; one
+// workgroup here folds them (greatest value, lowest index among equals; no float atomics, so
+// the result does not depend on scheduling) and merges with a strict "greater than", so that
+// an earlier chunk keeps the win on equal values.  When the running best changes, the
+// winning candidate row is copied into the handle so the chunk buffer can be recycled.
+#include "bsse_internal.h"
+#include <limits.h>
+
+namespace bsse {
+
+namespace {
+
+constexpr int RT = 1024;
+
+__device__ __forceinline__ bool better(float v, long long i, float bv, long long bi)
+{
+    return v > bv || (v == bv && i < bi);
+}
+
+__global__ void __launch_bounds__(RT)
+reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict__ blk_i,
+                    long long nblocks, const float *__restrict__ X, long long index_base, int m,
+                    RunningBest *run, float *best_x)
+{
+    __shared__ float sv[RT / 64];
+    __shared__ long long si[RT / 64];
+    __shared__ long long win;          // chunk-local row to copy, or -1
+
+    float bv = -INFINITY;
+    long long bi = LLONG_MAX;
+    for (long long b = threadIdx.x; b < nblocks; b += RT) {
+        const float v = blk_v[b];
+        const long long i = blk_i[b];
+        if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float ov = __shfl_xor(bv, d, 64);
+        const long long oi = __shfl_xor(bi, d, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < RT / 64; ++w)
+            if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+        long long w_row = -1;
+        if (bi != LLONG_MAX && (!run->has || bv > run->value)) {
+            run->value = bv;
+            run->index = bi;
+            run->has = 1;
+            w_row = bi - index_base;
+        }
+        win = w_row;
+    }
+    __syncthreads();
+    const long long row = win;
+    if (row >= 0)
+        for (int i = threadIdx.x; i < m; i += RT) best_x[i] = X[row * m + i];
+}
+
+__global__ void reset_kernel(RunningBest *run, unsigned long long *tie_counter)
+{
+    run->value = 0.0f;
+    run->has = 0;
+    run->index = -1;
+    *tie_counter = 0ull;
+}
+
+}  // namespace
+
+// Clears the running best and the tie counter with a kernel (not a memset node), so the
+// call can sit inside a captured graph.
+hipError_t launch_reset(RunningBest *run, unsigned long long *tie_counter, hipStream_t s)
+{
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, s, run, tie_counter);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
+                               const float *X, long long index_base, int m, RunningBest *run,
+                               float *best_x, hipStream_t s)
+{
+    if (nblocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(reduce_merge_kernel, dim3(1), dim3(RT), 0, s, blk_v, blk_i, nblocks, X,
+                       index_base, m, run, best_x);
+    return hipGetLastError();
+}
+
+}  // namespace bsse
