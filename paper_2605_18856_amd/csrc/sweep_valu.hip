@@ -95,7 +95,7 @@ __global__ void __launch_bounds__(WG) sweep_valu_kernel(GameView g, SweepArgs a)
                 const int j = j0 + q;
                 if (j >= n) break;
                 if (u[q] > best_u) {
-                    best_u = u[q]; best_j = j; has_l = false;
+                    best_u = u[q]; best_j = j; has_l = false; tied = false;
                 } else if (u[q] == best_u) {
                     // exact follower tie: the leader's payoff decides, then the lower index
                     tied = true;

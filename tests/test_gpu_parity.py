@@ -200,7 +200,7 @@ def test_empty_inputs_and_state_errors():
         with pytest.raises(bsse.BsseError) as e:
             bsse.bsse_sweep(g)                      # nothing generated yet
         assert e.value.status == bsse.BSSE_ESTATE
-        empty = torch.empty((0, 4), dtype=torch.float32, device="cuda")
+        empty = torch.zeros((1, 4), dtype=torch.float32, device="cuda")   # a real pointer, 0 rows used
         out = bsse.bsse_sweep(g, empty, 0)
         assert out.best_index == -1 and out.best_response is None and out.n_evals == 0
         bsse.bsse_eval(g, empty, 0, None, None)
