@@ -1,0 +1,140 @@
+"""GPU parity tests of the matrix-core (MFMA) sweep kernels against the CPU oracle, through
+the C ABI.  Small cases are compared element by element; the benchmark configurations are
+run at full size in the launch shape bench.py times and compared on sampled candidates."""
+import numpy as np
+import pytest
+
+from oracle import sweep as osweep
+from paper_2605_18856_amd import bsse, workloads
+from tests import parity
+from tests.test_gpu_parity import _full_check, _make, _run_eval, _torch
+
+pytestmark = pytest.mark.gpu
+
+# (m, n, K, storage): every instantiated (m_pad, n) variant, with and without padding of m
+# and of the type count
+MFMA_SHAPES = [
+    (8, 8, 4, "f32"), (8, 8, 3, "f32"), (5, 8, 9, "f32"),
+    (16, 16, 3, "f32"), (12, 16, 2, "f32"),
+    (32, 32, 16, "f32"), (20, 32, 5, "f32"),
+    (32, 64, 3, "f32"), (24, 64, 2, "f32"),
+    (128, 256, 2, "f32"), (100, 256, 1, "f32"),
+    (16, 32, 3, "bf16"), (32, 16, 5, "bf16"), (9, 32, 2, "bf16"),
+    (64, 128, 4, "bf16"), (50, 128, 2, "bf16"),
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_SHAPES, ids=lambda s: "m%dn%dK%d%s" % s)
+@pytest.mark.parametrize("count", [1, 33, 1300])
+def test_mfma_path_parity(shape, count):
+    m, n, K, storage = shape
+    game = workloads.small_game(m, n, K, 500 + m + n + K, kind="normal", storage=storage)
+    X = workloads.host_candidates(m, count, 11 + count, "dirichlet")
+    _full_check(game, X, bsse.BSSE_PATH_MFMA, "mfma")
+
+
+@pytest.mark.parametrize("shape", [(8, 8, 5, "f32"), (16, 16, 3, "f32"), (32, 32, 3, "f32"),
+                                   (32, 64, 2, "f32"), (16, 32, 3, "bf16"), (64, 128, 2, "bf16")],
+                         ids=lambda s: "m%dn%dK%d%s" % s)
+@pytest.mark.parametrize("kind", ["dyadic", "vertex"])
+def test_mfma_exact_ties(shape, kind):
+    """Integer payoffs with duplicated follower columns and exactly representable candidates:
+    every product and partial sum is exact in any order, so both sides see the same ties and
+    best responses must agree with no exception."""
+    m, n, K, storage = shape
+    game = workloads.small_game(m, n, K, 77, kind="dup", storage=storage)
+    X = workloads.host_candidates(m, 700, 78, kind)
+    rep, out = _full_check(game, X, bsse.BSSE_PATH_MFMA, "mfma")
+    assert rep.br_mismatch == 0
+    ref = osweep.sweep(game.A, game.B, game.prior, X, diagnostics=True)
+    assert (ref.gap == 0).sum() > 0
+    assert out.n_tie_evals == int((ref.gap == 0).sum())
+
+
+def test_mfma_and_valu_paths_agree_on_hand_cases():
+    """2x2 hand game embedded in an 8x8 shape: the tie-break decides the optimum."""
+    A = np.zeros((1, 8, 8), np.float32)
+    B = np.full((1, 8, 8), -5.0, np.float32)
+    A[0, :2, :2] = [[2, 4], [1, 3]]
+    B[0, :2, :2] = [[1, 0], [0, 1]]
+    X = np.zeros((101, 8), np.float32)
+    X[:, 0] = np.arange(101) / np.float32(100)
+    X[:, 1] = np.float32(1) - X[:, 0]
+    for path in (bsse.BSSE_PATH_VALU, bsse.BSSE_PATH_MFMA):
+        with bsse.bsse_create(8, 8, 1, A, B, np.array([1.0], np.float32), path=path) as g:
+            Xd = _torch().from_numpy(X).cuda()
+            out = bsse.bsse_sweep(g, Xd, 101)
+            assert out.best_index == 50 and out.best_value == 3.5 and out.best_response[0] == 1
+
+
+def _sampled_check(game, count, sample_rows, chunk=None):
+    """Full-size run in bench.py's launch shape; oracle on a sample of rows + the winner."""
+    torch = _torch()
+    tol = parity.TOL_BF16 if game.storage == "bf16" else parity.TOL_F32
+    with _make(game) as g:
+        assert bsse.bsse_path_name(g).startswith("mfma")
+        Xd = torch.empty((count, game.m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, game.candidate_seed, 0, count, Xd)
+        V = torch.empty(count, dtype=torch.float32, device="cuda")
+        br = torch.empty((count, game.K), dtype=torch.int32, device="cuda")
+        bsse.bsse_eval(g, Xd, count, V, br)
+        out = bsse.bsse_sweep(g, Xd, count)
+        torch.cuda.synchronize()
+        # reduction: CPU arg-max (first maximum) over the GPU's own values, bit-exact
+        Vh = V.cpu().numpy()
+        c_cpu = int(np.argmax(Vh))
+        assert out.best_index == c_cpu and np.float32(out.best_value) == Vh[c_cpu]
+        rows = np.unique(np.concatenate([np.arange(min(sample_rows // 2, count)),
+                                         np.linspace(0, count - 1, sample_rows // 2).astype(np.int64),
+                                         [out.best_index]]))
+        idx = torch.from_numpy(rows).cuda()
+        Xs = Xd[idx].cpu().numpy()
+        rep = parity.compare_eval(game, Xs, Vh[rows], br[idx].cpu().numpy(), tol)
+        parity.check_report(rep, tol)
+        assert np.array_equal(out.best_response, br[out.best_index].cpu().numpy())
+        if chunk:
+            bsse.bsse_sweep_reset(g)
+            for a in range(0, count, chunk):
+                b = min(count, a + chunk)
+                bsse.bsse_sweep_chunk(g, Xd[a:b], b - a, a)
+            parts = bsse.bsse_sweep_result(g)
+            assert (parts.best_index, parts.best_value) == (out.best_index, out.best_value)
+        return rep
+
+
+def test_config2_full_size():
+    rep = _sampled_check(workloads.game(2), 1 << 20, 1 << 16, chunk=(1 << 18) + 3)
+    assert rep.n_evals >= (1 << 16) * 4 // 2
+
+
+def test_config3_full_size_sampled():
+    _sampled_check(workloads.game(3), 1 << 24, 8192)
+
+
+def test_config4_one_chunk_sampled():
+    _sampled_check(workloads.game(4), 1 << 22, 1024)
+
+
+def test_config5_subrange_sampled():
+    _sampled_check(workloads.game(5), 1 << 14, 256)
+
+
+def test_config5_tie_injected_variant():
+    """Duplicated follower columns at the benchmark shape: the leader-favourable rule and the
+    lowest-index rule decide a large share of the evaluations."""
+    game = workloads.game(5, "ties")
+    torch = _torch()
+    count = 384
+    X = np.concatenate([workloads.host_candidates(game.m, count - 128, 5, "dirichlet"),
+                        workloads.host_candidates(game.m, 64, 6, "vertex"),
+                        workloads.host_candidates(game.m, 64, 7, "dyadic")])
+    with _make(game) as g:
+        Xd, V, br = _run_eval(g, X)
+        rep = parity.compare_eval(game, X, V, br)
+        parity.check_report(rep, parity.TOL_F32)
+        out = bsse.bsse_sweep(g, Xd, count)
+        ref = osweep.sweep(game.A, game.B, game.prior, X[-128:], diagnostics=True, nthreads=8)
+        # exactly representable candidates: ties are exact on both sides, so are the answers
+        assert np.array_equal(br[-128:], ref.br)
+        assert (ref.gap == 0).sum() > 1000
+        assert out.n_tie_evals >= int((ref.gap == 0).sum())
