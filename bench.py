@@ -95,22 +95,33 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     if want_cpu_baseline:
         from oracle import sweep as osweep
         cores = len(os.sched_getaffinity(0))
-        # bounded sample: enough candidates for roughly 10-30 s of oracle work on this host
-        per_eval_flops = 4.0 * game.m * game.n + 2.0 * game.m       # the oracle walks B twice
-        budget = 2.0e9 * cores * 15.0 / 8.0                         # ~0.25 GFLOP/s/core, plain loops
-        sample = int(min(count, max(64, budget / (per_eval_flops * game.K))))
+        # bounded sample: calibrate on a few rows, then size the sample for ~12 s of oracle
+        # work; when the whole batch takes less, repeat passes over the batch instead
         if lattice:
-            Xh = bsse.candidates_to_host(g)[:sample]
+            Xall = bsse.candidates_to_host(g)
         else:
-            Xh = Xd[:sample].cpu().numpy()
-        if game.storage == "bf16":
-            Xh = workloads.round_to_bf16(Xh)
+            Xall = None
+        def rows(k):
+            Xh = Xall[:k] if lattice else Xd[:k].cpu().numpy()
+            return workloads.round_to_bf16(Xh) if game.storage == "bf16" else Xh
+        probe = int(min(count, max(16, 2_000_000 // (game.K * game.m * game.n))))
+        Xp = rows(probe)
+        osweep.sweep(game.A, game.B, game.prior, Xp[:2], per_candidate=False, nthreads=cores)
         c0 = time.perf_counter()
-        ref = osweep.sweep(game.A, game.B, game.prior, Xh, per_candidate=False, nthreads=cores)
+        osweep.sweep(game.A, game.B, game.prior, Xp, per_candidate=False, nthreads=cores)
+        per_row = max((time.perf_counter() - c0) / probe, 1e-9)
+        sample = int(min(count, max(probe, 12.0 / per_row)))
+        passes = max(1, int(12.0 / (per_row * sample))) if sample == count else 1
+        passes = min(passes, 2000)
+        Xh = rows(sample)
+        c0 = time.perf_counter()
+        for _ in range(passes):
+            ref = osweep.sweep(game.A, game.B, game.prior, Xh, per_candidate=False, nthreads=cores)
         c1 = time.perf_counter()
-        cpu = {"value": sample * game.K / (c1 - c0), "unit": "candidate-type evals/s",
+        cpu = {"value": passes * sample * game.K / (c1 - c0), "unit": "candidate-type evals/s",
                "cores": ref.threads, "kind": "oracle",
-               "sample": f"first {sample} candidates of the step's batch ({c1 - c0:.2f} s)"}
+               "sample": f"{passes} pass(es) over the first {sample} candidates of the step's "
+                         f"batch of {count} ({c1 - c0:.1f} s of oracle time, fp64, OpenMP over candidates)"}
     g.close()
     return {
         "ms_per_step": ms_per_step, "value": value, "path": path, "count": count,

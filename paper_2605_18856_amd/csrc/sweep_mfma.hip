@@ -17,16 +17,16 @@
 // per-lane fragment order, so staging a row tile into LDS is a flat copy and the operand
 // reads are conflict-free.
 //
-// Ties.  The streaming arg-max keeps, per lane, (best value, its action) with a strict ">"
-// in ascending action order, and a wave-wide bit mask (scalar registers) that records whether
-// the current best has been met again exactly.  Only if some candidate of the tile ends a
-// type with that bit set (or ties with its partner lane) does the wavefront take the
-// second pass for that type, which recomputes the same MFMA tiles (bit-identical) and walks
-// the exact maximisers in ascending action order comparing leader payoffs.
+// Ties.  The accumulators of a whole type stay in registers; the arg-max is a max3 chain, one
+// exchange with the partner lane, then compare-equal + select.  The compare masks are counted
+// on the scalar unit: anything other than one hit per candidate sends the wavefront through
+// an exact routine for that type, which recomputes the same MFMA tiles (bit-identical) and
+// walks the exact maximisers in ascending action order comparing leader payoffs.
 #include "bsse_internal.h"
 #include <limits.h>
 #include <stdlib.h>
 #include <string.h>
+#include <type_traits>
 
 namespace bsse {
 
@@ -134,24 +134,84 @@ template <int MP> struct Path<__bf16, MP> {
 // Row of a 32x32 accumulator tile held in register r, without the lane-half term 4*(lane/32).
 __device__ __host__ constexpr int acc_row_base(int r) { return 8 * (r / 4) + (r % 4); }
 
+// Partner-lane helpers built on v_permlane32_swap: the two results hold, in every lane, the
+// value of the lane with the same column in the lower half and in the upper half, so any
+// commutative combination of them is the pair's result, identical in both lanes.
+__device__ __forceinline__ float pair_max(float v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ int pair_min(int v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return min((int)r[0], (int)r[1]);
+}
+__device__ __forceinline__ float pair_sum(float v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = Begin, Begin+Step, ... (Step may be
+// negative), so that loop indices can feed immediate operands.
+template <int I, int End, int Step, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr ((Step > 0 && I < End) || (Step < 0 && I > End)) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + Step, End, Step>(f);
+    }
+}
+
+// One step of the "which register holds the maximum" pass, pinned to four instructions:
+//   vcc  = (u != gmax)                      v_cmp_neq_f32
+//   idx  = vcc ? idx : JC                   v_cndmask_b32   (JC is an inline constant, 0..64:
+//                                           a literal would be a second constant-bus read)
+//   hits += number of lanes with u == gmax  s_bcnt0_i32_b64 + s_add_i32 (scalar unit)
+// Written as one asm block so that the 64-bit compare mask lives only in vcc; left to the
+// scheduler, the masks of many steps were kept alive at once and spilled.
+template <int JC>
+__device__ __forceinline__ void match_step(float u, float gmax, int &idx, int &hits)
+{
+    static_assert(JC >= 0 && JC <= 64, "must be an inline constant");
+    int tmp;
+    asm("v_cmp_neq_f32 vcc, %3, %4\n\t"
+        "v_cndmask_b32 %0, %5, %0, vcc\n\t"
+        "s_bcnt0_i32_b64 %2, vcc\n\t"
+        "s_add_i32 %1, %1, %2"
+        : "+v"(idx), "+s"(hits), "=&s"(tmp)
+        : "v"(u), "v"(gmax), "i"(JC)
+        : "vcc", "scc");
+}
+
 // ------------------------------------------------------------------------------------------
 // T: float | __bf16.  MP: padded m.  N: follower actions (8, 16 or a multiple of 32).
 // NT: 32-candidate tiles per wavefront.  WAVES: wavefronts per workgroup.
-// STAGE_TILES: 32-row tiles of packed follower payoffs per LDS stage.
-template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES>
-__global__ void __launch_bounds__(WAVES * 64)
+// STAGE_TILES: 32-row tiles of packed follower payoffs per LDS stage.  OCC: wavefronts per
+// SIMD the register allocation is held to.
+//
+// A "group" is the set of row tiles that holds whole types: N/32 tiles of one type when
+// N >= 32, one tile of 32/N types otherwise.  The accumulators of a whole group stay in
+// registers (N/2 per lane and candidate tile when N >= 32), so the arg-max is two passes
+// over registers: a max3 chain for the lane's maximum, one exchange with the partner lane
+// for the pair's maximum, then compare-equal + select in descending action order, which
+// leaves the lowest maximising action.  The compare masks are population-counted on the
+// scalar unit; a total other than one hit per candidate means an exact tie somewhere in the
+// tile and sends the wavefront through the exact routine for that type.
+template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC>
+__global__ void __launch_bounds__(WAVES * 64, OCC)
 sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 {
     typedef Path<T, MP> P;
     typedef typename P::frag frag;
     typedef typename P::xreg xreg;
     constexpr int KS = P::KSTEPS, HALF = P::HALF;
-    constexpr int TPG = N >= 32 ? N / 32 : 1;          // row tiles per group of whole types
+    constexpr int TPG = N >= 32 ? N / 32 : 1;          // row tiles per group
     constexpr int TYPES = N >= 32 ? 1 : 32 / N;        // types per group
     static_assert(N == 8 || N == 16 || N % 32 == 0, "unsupported action count");
     static_assert(STAGE_TILES % TPG == 0 || TPG % STAGE_TILES == 0, "stage/group mismatch");
     constexpr int TILE_FRAGS = KS * 64;                 // fragments per row tile
-    constexpr int STAGE_FRAGS = STAGE_TILES * TILE_FRAGS;
+    constexpr int NO_ACTION = 1 << 20;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     frag *stage = reinterpret_cast<frag *>(smem);
@@ -167,7 +227,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 
     // ---- candidate rows into registers: lane (col, h) keeps x[c][h*HALF .. h*HALF+HALF)
     xreg x[NT][P::XREGS];
-    unsigned long long valid_pairs[NT];       // bit l set iff lane l's candidate exists
+    unsigned valid32[NT];                     // bit c set iff candidate c of the tile exists
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
         const long long c = wave_base + ct * 32 + col;
@@ -185,7 +245,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             for (int e = 0; e < HALF; ++e) v[e] = (ok && h * HALF + e < m) ? row[e] : 0.0f;
         }
         P::pack_x(v, x[ct]);
-        valid_pairs[ct] = __builtin_amdgcn_ballot_w64(ok);
+        valid32[ct] = (unsigned)__builtin_amdgcn_ballot_w64(ok);
     }
 
     float V[NT];
@@ -193,55 +253,13 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     for (int ct = 0; ct < NT; ++ct) V[ct] = 0.0f;
     unsigned tie_count = 0;                   // wave-uniform
 
-    // streaming arg-max state of the current group
-    float best[NT][TYPES];
-    int bidx[NT][TYPES];
-    unsigned long long tie[NT][TYPES];
-
-    auto reset_state = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-            for (int ti = 0; ti < TYPES; ++ti) { best[ct][ti] = -INFINITY; bidx[ct][ti] = 0; tie[ct][ti] = 0ull; }
-    };
-
-    // one 32-row tile (index tt inside its group) against all NT candidate tiles
-    auto tile_pass = [&](const frag *afrags, int tt) __attribute__((always_inline)) {
-        f32x16 acc[NT];
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const frag af = afrags[s * 64 + lane];
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) acc[ct] = P::mfma(af, x[ct], s, acc[ct]);
-        }
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rb = tt * 32 + acc_row_base(r);      // row in group, minus 4h
-                const int ti = N >= 32 ? 0 : rb / N;           // rb and rb+4 share a type (N % 8 == 0)
-                const int jc = N >= 32 ? rb : rb % N;          // action, minus 4h
-                const float u = acc[ct][r];
-                const bool gt = u > best[ct][ti];
-                const unsigned long long mgt = __builtin_amdgcn_ballot_w64(gt);
-                const unsigned long long meq = __builtin_amdgcn_ballot_w64(u == best[ct][ti]);
-                best[ct][ti] = gt ? u : best[ct][ti];
-                bidx[ct][ti] = gt ? jc : bidx[ct][ti];
-                tie[ct][ti] = (tie[ct][ti] & ~mgt) | meq;
-            }
-    };
-
-    // second pass for one (candidate tile, type): exact maximisers in ascending action order,
-    // leader payoff decides, then the lower action.  Reads fragments from global memory.
-    auto second_pass = [&](int ct, int group, int ti, int t, float ubest, unsigned tied32,
-                           float &l_out, int &j_out) __attribute__((always_inline)) {
+    // Exact routine for one (candidate tile, type): recomputes the type's tiles one at a time
+    // (same instruction sequence, hence the same bits), visits the exact maximisers in
+    // ascending action order, lets the leader's payoff decide and then the lower action.
+    auto exact_type = [&](int ct, int group, int ti, int t, float gmax, float &l_out,
+                          int &j_out) __attribute__((always_inline)) {
         float lbest = 0.0f;
-        int jbest = 0;
-        bool has = false;
+        int jbest = 0, nmatch = 0;
         const unsigned char *ATt = ATpack + (size_t)t * N * MP * sizeof(T);
 #pragma unroll 1
         for (int tt = 0; tt < TPG; ++tt) {
@@ -258,67 +276,113 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
                         const int r = 4 * q + rr;
-                        const int rb = tt * 32 + acc_row_base(r);
+                        const int rb = acc_row_base(r);
                         if (N < 32 && rb / N != ti) continue;
-                        const int j = (N >= 32 ? rb : rb % N) + 4 * hh;
-                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc[r] == ubest);
-                        const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & tied32;
+                        const int j = (N >= 32 ? tt * 32 + rb : rb % N) + 4 * hh;
+                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc[r] == gmax);
+                        const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid32[ct];
                         if (hit == 0u) continue;                       // wave-uniform
-                        float l = P::half_dot(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T));
-                        l += __shfl_xor(l, 32, 64);
-                        const bool mine = (hit >> col) & 1u;
-                        if (mine && (!has || l > lbest)) { lbest = l; jbest = j; has = true; }
+                        const float l = pair_sum(
+                            P::half_dot(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T)));
+                        if ((hit >> col) & 1u) {
+                            if (nmatch == 0 || l > lbest) { lbest = l; jbest = j; }
+                            ++nmatch;
+                        }
                     }
         }
-        if (has) { l_out = lbest; j_out = jbest; }
+        l_out = lbest; j_out = jbest;
+        tie_count += __builtin_popcount((unsigned)__builtin_amdgcn_ballot_w64(nmatch >= 2));
     };
 
-    // close the types of one finished group
-    auto finish_group = [&](int group) __attribute__((always_inline)) {
+    // accumulators of the current group, all NT candidate tiles
+    f32x16 acc[NT][TPG];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int ti = 0; ti < TYPES; ++ti) {
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int tt = 0; tt < TPG; ++tt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ct][tt][r] = 0.0f;
+    };
+    // MFMAs of row tile tt of the group (fragments in LDS) against all NT candidate tiles
+    auto mfma_tile = [&](const frag *tf, int tt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const frag af = tf[s * 64 + lane];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(af, x[ct], s, acc[ct][tt]);
+        }
+    };
+    // per-type epilogue of a finished group
+    auto epilogue = [&](int group) __attribute__((always_inline)) {
+        static_for<0, TYPES, 1>([&](auto tic) {
+            constexpr int ti = decltype(tic)::value;
             const int t = group * TYPES + ti;
-            if (t >= K) break;                                          // padded type rows
+            if (t >= K) return;                                         // padded type rows
             const unsigned char *ATt = ATpack + (size_t)t * N * MP * sizeof(T);
             const float pt = g.prior[t];
+            float gmax[NT];
+            int jstar[NT];
+            bool clean[NT];
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
-                const float mine = best[ct][ti];
-                const int jmine = bidx[ct][ti] + 4 * h;
-                const float other = __shfl_xor(mine, 32, 64);
-                const int jother = __shfl_xor(jmine, 32, 64);
-                const bool take = other > mine || (other == mine && jother < jmine);
-                const unsigned long long mtake = __builtin_amdgcn_ballot_w64(take);
-                const unsigned long long mcross = __builtin_amdgcn_ballot_w64(other == mine);
-                const unsigned long long tm = tie[ct][ti];
-                const unsigned long long trot = (tm >> 32) | (tm << 32);
-                const unsigned long long tfin = ((tm & ~mtake) | (trot & mtake) | mcross) & valid_pairs[ct];
-                const float ubest = take ? other : mine;
-                int jstar = take ? jother : jmine;
-                float l = P::half_dot(x[ct], ATt + ((size_t)jstar * MP + h * HALF) * sizeof(T));
-                l += __shfl_xor(l, 32, 64);
-                const unsigned tied32 = (unsigned)tfin | (unsigned)(tfin >> 32);
-                if (tied32 != 0u) {                                     // wave-uniform, rare
-                    second_pass(ct, group, ti, t, ubest, tied32, l, jstar);
-                    tie_count += __builtin_popcount(tied32);
+                // lane maximum over this type's registers
+                float pm = -INFINITY;
+                float pend[2];
+                int np = 0;
+#pragma unroll
+                for (int tt = 0; tt < TPG; ++tt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if (N < 32 && acc_row_base(r) / N != ti) continue;
+                        pend[np++] = acc[ct][tt][r];
+                        if (np == 2) { pm = fmaxf(fmaxf(pm, pend[0]), pend[1]); np = 0; }
+                    }
+                if (np == 1) pm = fmaxf(pm, pend[0]);
+                const float gm = pair_max(pm);
+                // lowest maximising action of this lane; hits counted over the wavefront
+                int idx = NO_ACTION;
+                int hits = 0;
+                static_for<TPG * 16 - 1, -1, -1>([&](auto e) {
+                    constexpr int tt = decltype(e)::value / 16, r = decltype(e)::value % 16;
+                    constexpr int rb = acc_row_base(r);
+                    if constexpr (N >= 32 || rb / N == ti) {
+                        // immediates stay within a tile (inline constants); stepping down to
+                        // the next lower tile shifts what was found above by one tile
+                        if constexpr (r == 15 && tt < TPG - 1) idx += 32;
+                        constexpr int jc = N >= 32 ? rb : rb % N;
+                        match_step<jc>(acc[ct][tt][r], gm, idx, hits);
+                    }
+                });
+                gmax[ct] = gm;
+                jstar[ct] = pair_min(idx + 4 * h);
+                clean[ct] = hits == 32 && valid32[ct] == 0xFFFFFFFFu;     // wave-uniform
+            }
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                float l;
+                int js = jstar[ct];
+                if (clean[ct]) {
+                    l = pair_sum(P::half_dot(x[ct], ATt + ((size_t)js * MP + h * HALF) * sizeof(T)));
+                } else {
+                    exact_type(ct, group, ti, t, gmax[ct], l, js);
                 }
                 V[ct] = fmaf(pt, l, V[ct]);
                 if (a.br_out) {
                     const long long c = wave_base + ct * 32 + col;
-                    if (h == 0 && c < a.count) a.br_out[c * K + t] = jstar;
+                    if (h == 0 && c < a.count) a.br_out[c * K + t] = js;
                 }
             }
-        }
+        });
     };
 
     auto load_stage = [&](int first_tile, int ntiles) __attribute__((always_inline)) {
-        // flat copy of ntiles packed row tiles; all wavefronts of the workgroup take part
+        // flat copy of packed row tiles; all wavefronts of the workgroup take part
         const frag *src = Bpack + (size_t)first_tile * TILE_FRAGS;
         __syncthreads();                       // everyone is done with the previous stage
         for (int e = tid; e < ntiles * TILE_FRAGS; e += WAVES * 64) stage[e] = src[e];
         __syncthreads();
     };
-
     const int groups = row_tiles / TPG;
     if constexpr (STAGE_TILES >= TPG) {
         constexpr int GPS = STAGE_TILES / TPG;                          // groups per stage
@@ -328,28 +392,27 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             load_stage(g0 * TPG, ng * TPG);
 #pragma unroll 1
             for (int gi = 0; gi < ng; ++gi) {
-                reset_state();
+                zero_acc();
 #pragma unroll
-                for (int tt = 0; tt < TPG; ++tt) tile_pass(stage + (gi * TPG + tt) * TILE_FRAGS, tt);
-                finish_group(g0 + gi);
+                for (int tt = 0; tt < TPG; ++tt) mfma_tile(stage + (size_t)(gi * TPG + tt) * TILE_FRAGS, tt);
+                epilogue(g0 + gi);
             }
         }
     } else {
         constexpr int SPG = TPG / STAGE_TILES;                          // stages per group
 #pragma unroll 1
         for (int gr = 0; gr < groups; ++gr) {
-            reset_state();
+            zero_acc();
 #pragma unroll
             for (int ss = 0; ss < SPG; ++ss) {
                 load_stage(gr * TPG + ss * STAGE_TILES, STAGE_TILES);
 #pragma unroll
                 for (int t2 = 0; t2 < STAGE_TILES; ++t2)
-                    tile_pass(stage + t2 * TILE_FRAGS, ss * STAGE_TILES + t2);
+                    mfma_tile(stage + (size_t)t2 * TILE_FRAGS, ss * STAGE_TILES + t2);
             }
-            finish_group(gr);
+            epilogue(gr);
         }
     }
-    (void)STAGE_FRAGS;
 
     // ---- outputs
     if (a.V_out) {
@@ -397,20 +460,20 @@ struct Variant {
     int frag_bytes_per_tile;     // bytes of one packed 32-row tile
 };
 
-#define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv) \
-    { ST, MPv, Nv, NTv, Wv, STv, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv>, 32 * MPv * (int)sizeof(T) }
+#define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv, OCCv) \
+    { ST, MPv, Nv, NTv, Wv, STv, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv, OCCv>, 32 * MPv * (int)sizeof(T) }
 
 const Variant kVariants[] = {
     // fp32 payoffs
-    BSSE_VARIANT(float, 0, 8, 8, 4, 4, 1),
-    BSSE_VARIANT(float, 0, 16, 16, 4, 4, 2),
-    BSSE_VARIANT(float, 0, 32, 32, 4, 4, 16),
-    BSSE_VARIANT(float, 0, 32, 64, 2, 4, 8),
-    BSSE_VARIANT(float, 0, 128, 256, 2, 4, 2),
+    BSSE_VARIANT(float, 0, 8, 8, 4, 4, 1, 2),
+    BSSE_VARIANT(float, 0, 16, 16, 4, 4, 2, 2),
+    BSSE_VARIANT(float, 0, 32, 32, 4, 4, 16, 2),
+    BSSE_VARIANT(float, 0, 32, 64, 2, 4, 8, 2),
+    BSSE_VARIANT(float, 0, 128, 256, 1, 4, 2, 2),
     // bf16 payoffs
-    BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 8),
-    BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 8),
-    BSSE_VARIANT(__bf16, 1, 64, 128, 4, 4, 4),
+    BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 8, 2),
+    BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 8, 2),
+    BSSE_VARIANT(__bf16, 1, 64, 128, 2, 4, 4, 2),
 };
 
 const Variant *find_variant(int m, int n, int storage)
