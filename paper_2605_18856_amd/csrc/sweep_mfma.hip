@@ -185,10 +185,38 @@ __device__ __forceinline__ void match_step(float u, float gmax, int &idx, int &h
 }
 
 // ------------------------------------------------------------------------------------------
+// Stage records.  The packed follower payoffs are cut into "stages" of STAGE_TILES 32-row
+// tiles; when AT_LDS, the leader-payoff rows of the types a stage covers follow its tiles, so
+// that one flat asynchronous copy (global_load_lds) brings everything a stage needs into LDS.
+// Leader rows in LDS are padded by 16 bytes so that gathers of different rows spread over
+// banks.  The record size is rounded to what one sweep of all wavefronts copies (1 KiB each).
+struct Geometry {
+    int tile_bytes, tpg, types, ts, ats, at_bytes, rec_bytes;
+};
+__host__ __device__ constexpr Geometry make_geometry(int esz, int mp, int n, int stage_tiles,
+                                                     int waves, bool at_lds)
+{
+    Geometry q{};
+    q.tile_bytes = 32 * mp * esz;
+    q.tpg = n >= 32 ? n / 32 : 1;
+    q.types = n >= 32 ? 1 : 32 / n;
+    q.ts = stage_tiles >= q.tpg ? (stage_tiles / q.tpg) * q.types : 0;     // whole types per stage
+    q.ats = mp + 16 / esz;
+    q.at_bytes = at_lds ? q.ts * n * q.ats * esz : 0;
+    const int unit = waves * 1024;
+    q.rec_bytes = (stage_tiles * q.tile_bytes + q.at_bytes + unit - 1) / unit * unit;
+    return q;
+}
+
+typedef const void __attribute__((address_space(1))) *global_ptr;
+typedef void __attribute__((address_space(3))) *lds_ptr;
+
+// ------------------------------------------------------------------------------------------
 // T: float | __bf16.  MP: padded m.  N: follower actions (8, 16 or a multiple of 32).
 // NT: 32-candidate tiles per wavefront.  WAVES: wavefronts per workgroup.
-// STAGE_TILES: 32-row tiles of packed follower payoffs per LDS stage.  OCC: wavefronts per
-// SIMD the register allocation is held to.
+// STAGE_TILES: row tiles per LDS stage.  OCC: wavefronts per SIMD the register allocation is
+// held to.  AT_LDS: leader-payoff rows travel with the stage (else they are gathered from
+// global memory / L2).
 //
 // A "group" is the set of row tiles that holds whole types: N/32 tiles of one type when
 // N >= 32, one tile of 32/N types otherwise.  The accumulators of a whole group stay in
@@ -198,7 +226,10 @@ __device__ __forceinline__ void match_step(float u, float gmax, int &idx, int &h
 // leaves the lowest maximising action.  The compare masks are population-counted on the
 // scalar unit; a total other than one hit per candidate means an exact tie somewhere in the
 // tile and sends the wavefront through the exact routine for that type.
-template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC>
+//
+// Stages are double-buffered: the copy of stage s+1 is issued (asynchronously, straight into
+// LDS) before the work on stage s and awaited after it, one workgroup barrier per stage.
+template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS>
 __global__ void __launch_bounds__(WAVES * 64, OCC)
 sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 {
@@ -206,24 +237,42 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     typedef typename P::frag frag;
     typedef typename P::xreg xreg;
     constexpr int KS = P::KSTEPS, HALF = P::HALF;
-    constexpr int TPG = N >= 32 ? N / 32 : 1;          // row tiles per group
-    constexpr int TYPES = N >= 32 ? 1 : 32 / N;        // types per group
+    constexpr Geometry G = make_geometry((int)sizeof(T), MP, N, STAGE_TILES, WAVES, AT_LDS);
+    constexpr int TPG = G.tpg, TYPES = G.types;
     static_assert(N == 8 || N == 16 || N % 32 == 0, "unsupported action count");
     static_assert(STAGE_TILES % TPG == 0 || TPG % STAGE_TILES == 0, "stage/group mismatch");
+    static_assert(!AT_LDS || STAGE_TILES >= TPG, "leader rows in LDS need whole types per stage");
     constexpr int TILE_FRAGS = KS * 64;                 // fragments per row tile
     constexpr int NO_ACTION = 1 << 20;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    frag *stage = reinterpret_cast<frag *>(smem);
     __shared__ float red_v[WAVES];
     __shared__ long long red_i[WAVES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, col = lane & 31;
     const int m = g.m, K = g.K;
-    const frag *Bpack = reinterpret_cast<const frag *>(g.Bpack);
+    const unsigned char *records = reinterpret_cast<const unsigned char *>(g.Bpack);
     const unsigned char *ATpack = reinterpret_cast<const unsigned char *>(g.ATpack);
     const long long wave_base = ((long long)blockIdx.x * WAVES + wave) * (NT * 32);
+    const int nstages = (row_tiles + STAGE_TILES - 1) / STAGE_TILES;
+
+    auto prefetch = [&](int st) __attribute__((always_inline)) {
+        const unsigned char *src = records + (size_t)st * G.rec_bytes;
+        unsigned char *dst = smem + (st & 1) * G.rec_bytes;
+#pragma unroll
+        for (int i = 0; i < G.rec_bytes / (WAVES * 1024); ++i) {
+            const int chunk = i * WAVES + wave;
+            __builtin_amdgcn_global_load_lds((global_ptr)(src + chunk * 1024 + lane * 16),
+                                             (lds_ptr)(dst + chunk * 1024), 16, 0, 0);
+        }
+    };
+    // own copies have landed; then everyone's have, and everyone is done with the old stage
+    auto stage_sync = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+    prefetch(0);
 
     // ---- candidate rows into registers: lane (col, h) keeps x[c][h*HALF .. h*HALF+HALF)
     xreg x[NT][P::XREGS];
@@ -254,8 +303,9 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     unsigned tie_count = 0;                   // wave-uniform
 
     // Exact routine for one (candidate tile, type): recomputes the type's tiles one at a time
-    // (same instruction sequence, hence the same bits), visits the exact maximisers in
-    // ascending action order, lets the leader's payoff decide and then the lower action.
+    // from the packed records in global memory (same instruction sequence, hence the same
+    // bits), visits the exact maximisers in ascending action order, lets the leader's payoff
+    // decide and then the lower action.
     auto exact_type = [&](int ct, int group, int ti, int t, float gmax, float &l_out,
                           int &j_out) __attribute__((always_inline)) {
         float lbest = 0.0f;
@@ -263,12 +313,14 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         const unsigned char *ATt = ATpack + (size_t)t * N * MP * sizeof(T);
 #pragma unroll 1
         for (int tt = 0; tt < TPG; ++tt) {
-            const frag *afrags = Bpack + ((size_t)group * TPG + tt) * TILE_FRAGS;
-            f32x16 acc;
+            const int gt = group * TPG + tt;
+            const frag *afrags = reinterpret_cast<const frag *>(
+                records + (size_t)(gt / STAGE_TILES) * G.rec_bytes + (size_t)(gt % STAGE_TILES) * G.tile_bytes);
+            f32x16 acc1;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) acc = P::mfma(afrags[s * 64 + lane], x[ct], s, acc);
+            for (int s = 0; s < KS; ++s) acc1 = P::mfma(afrags[s * 64 + lane], x[ct], s, acc1);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -279,7 +331,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                         const int rb = acc_row_base(r);
                         if (N < 32 && rb / N != ti) continue;
                         const int j = (N >= 32 ? tt * 32 + rb : rb % N) + 4 * hh;
-                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc[r] == gmax);
+                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc1[r] == gmax);
                         const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid32[ct];
                         if (hit == 0u) continue;                       // wave-uniform
                         const float l = pair_sum(
@@ -313,13 +365,12 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(af, x[ct], s, acc[ct][tt]);
         }
     };
-    // per-type epilogue of a finished group
-    auto epilogue = [&](int group) __attribute__((always_inline)) {
+    // per-type epilogue of a finished group; at_lds = LDS rows of the group's first type
+    auto epilogue = [&](int group, const unsigned char *at_lds) __attribute__((always_inline)) {
         static_for<0, TYPES, 1>([&](auto tic) {
             constexpr int ti = decltype(tic)::value;
             const int t = group * TYPES + ti;
             if (t >= K) return;                                         // padded type rows
-            const unsigned char *ATt = ATpack + (size_t)t * N * MP * sizeof(T);
             const float pt = g.prior[t];
             float gmax[NT];
             int jstar[NT];
@@ -363,7 +414,12 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 float l;
                 int js = jstar[ct];
                 if (clean[ct]) {
-                    l = pair_sum(P::half_dot(x[ct], ATt + ((size_t)js * MP + h * HALF) * sizeof(T)));
+                    float part;
+                    if constexpr (AT_LDS)
+                        part = P::half_dot(x[ct], at_lds + ((size_t)(ti * N + js) * G.ats + h * HALF) * sizeof(T));
+                    else
+                        part = P::half_dot(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
+                    l = pair_sum(part);
                 } else {
                     exact_type(ct, group, ti, t, gmax[ct], l, js);
                 }
@@ -376,41 +432,44 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         });
     };
 
-    auto load_stage = [&](int first_tile, int ntiles) __attribute__((always_inline)) {
-        // flat copy of packed row tiles; all wavefronts of the workgroup take part
-        const frag *src = Bpack + (size_t)first_tile * TILE_FRAGS;
-        __syncthreads();                       // everyone is done with the previous stage
-        for (int e = tid; e < ntiles * TILE_FRAGS; e += WAVES * 64) stage[e] = src[e];
-        __syncthreads();
-    };
+    stage_sync();                              // stage 0 is in LDS
     const int groups = row_tiles / TPG;
     if constexpr (STAGE_TILES >= TPG) {
         constexpr int GPS = STAGE_TILES / TPG;                          // groups per stage
 #pragma unroll 1
-        for (int g0 = 0; g0 < groups; g0 += GPS) {
+        for (int st = 0; st < nstages; ++st) {
+            if (st + 1 < nstages) prefetch(st + 1);
+            const unsigned char *buf = smem + (st & 1) * G.rec_bytes;
+            const frag *tiles = reinterpret_cast<const frag *>(buf);
+            const int g0 = st * GPS;
             const int ng = groups - g0 < GPS ? groups - g0 : GPS;
-            load_stage(g0 * TPG, ng * TPG);
 #pragma unroll 1
             for (int gi = 0; gi < ng; ++gi) {
                 zero_acc();
 #pragma unroll
-                for (int tt = 0; tt < TPG; ++tt) mfma_tile(stage + (size_t)(gi * TPG + tt) * TILE_FRAGS, tt);
-                epilogue(g0 + gi);
+                for (int tt = 0; tt < TPG; ++tt) mfma_tile(tiles + (size_t)(gi * TPG + tt) * TILE_FRAGS, tt);
+                epilogue(g0 + gi, buf + STAGE_TILES * G.tile_bytes + (size_t)gi * TYPES * N * G.ats * sizeof(T));
             }
+            stage_sync();
         }
     } else {
         constexpr int SPG = TPG / STAGE_TILES;                          // stages per group
+        int st = 0;
 #pragma unroll 1
         for (int gr = 0; gr < groups; ++gr) {
             zero_acc();
-#pragma unroll
-            for (int ss = 0; ss < SPG; ++ss) {
-                load_stage(gr * TPG + ss * STAGE_TILES, STAGE_TILES);
-#pragma unroll
-                for (int t2 = 0; t2 < STAGE_TILES; ++t2)
-                    mfma_tile(stage + (size_t)t2 * TILE_FRAGS, ss * STAGE_TILES + t2);
-            }
-            epilogue(gr);
+            static_for<0, SPG, 1>([&](auto ssc) {
+                constexpr int ss = decltype(ssc)::value;
+                if (st + 1 < nstages) prefetch(st + 1);
+                const frag *tiles = reinterpret_cast<const frag *>(smem + (st & 1) * G.rec_bytes);
+                static_for<0, STAGE_TILES, 1>([&](auto t2c) {
+                    constexpr int t2 = decltype(t2c)::value;
+                    mfma_tile(tiles + (size_t)t2 * TILE_FRAGS, ss * STAGE_TILES + t2);
+                });
+                if constexpr (ss == SPG - 1) epilogue(gr, nullptr);
+                stage_sync();
+                ++st;
+            });
         }
     }
 
@@ -456,24 +515,26 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 // Instantiation table.
 struct Variant {
     int storage, mp, n, nt, waves, stage_tiles;
+    bool at_lds;
     void (*kernel)(GameView, SweepArgs, int);
-    int frag_bytes_per_tile;     // bytes of one packed 32-row tile
+    Geometry geo;
 };
 
-#define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv, OCCv) \
-    { ST, MPv, Nv, NTv, Wv, STv, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv, OCCv>, 32 * MPv * (int)sizeof(T) }
+#define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv, OCCv, ATL)                                   \
+    { ST, MPv, Nv, NTv, Wv, STv, ATL, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv, OCCv, ATL>,   \
+      make_geometry((int)sizeof(T), MPv, Nv, STv, Wv, ATL) }
 
 const Variant kVariants[] = {
     // fp32 payoffs
-    BSSE_VARIANT(float, 0, 8, 8, 4, 4, 1, 2),
-    BSSE_VARIANT(float, 0, 16, 16, 4, 4, 2, 2),
-    BSSE_VARIANT(float, 0, 32, 32, 4, 4, 16, 2),
-    BSSE_VARIANT(float, 0, 32, 64, 2, 4, 8, 2),
-    BSSE_VARIANT(float, 0, 128, 256, 1, 4, 2, 2),
+    BSSE_VARIANT(float, 0, 8, 8, 4, 4, 1, 2, true),
+    BSSE_VARIANT(float, 0, 16, 16, 4, 4, 2, 2, true),
+    BSSE_VARIANT(float, 0, 32, 32, 4, 4, 4, 2, true),
+    BSSE_VARIANT(float, 0, 32, 64, 2, 4, 4, 2, true),
+    BSSE_VARIANT(float, 0, 128, 256, 1, 4, 2, 2, false),
     // bf16 payoffs
-    BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 8, 2),
-    BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 8, 2),
-    BSSE_VARIANT(__bf16, 1, 64, 128, 2, 4, 4, 2),
+    BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 2, 2, true),
+    BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 2, 2, false),
+    BSSE_VARIANT(__bf16, 1, 64, 128, 2, 4, 4, 2, true),
 };
 
 const Variant *find_variant(int m, int n, int storage)
@@ -509,34 +570,41 @@ hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &
     const Variant *v = find_variant(g.m, g.n, kind == PATH_MFMA_BF16 ? 1 : 0);
     if (!v) return hipErrorNotSupported;
     const long long blocks = mfma_num_blocks(g, kind, a.count);
-    const size_t lds = (size_t)v->stage_tiles * v->frag_bytes_per_tile;
+    const int tiles = row_tiles_for(*v, g.K);
+    const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
+    const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)v->kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(v->kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a,
-                       row_tiles_for(*v, g.K));
+    hipLaunchKernelGGL(v->kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
     return hipGetLastError();
 }
 
-// Host packing.  Bpack: [row tile][k-step][lane 0..63][fragment], where lane = 32*h + rowInTile
-// supplies leader actions i = h*MP/2 + (elements per lane)*s + e of (type, action) row
-// 32*tile + rowInTile; rows past K*n and actions past m are zero.  ATpack: [K][n][MP] in
-// natural action order (zero padded), so a lane's half of a column is contiguous.
+// Host packing.
+// Bpack = stage records (see Geometry): per stage, STAGE_TILES row tiles, each laid out as
+// [k-step][lane 0..63][fragment], where lane = 32*h + rowInTile supplies leader actions
+// i = h*MP/2 + (elements per lane)*s + e of (type, action) row 32*tile + rowInTile; then, when
+// the variant keeps leader rows in LDS, the rows [type slot][action][MP + pad] of the types the
+// stage covers.  Rows past K*n and actions past m are zero.
+// ATpack = [K][n][MP] leader payoffs in natural action order (zero padded), so that a lane's
+// half of a column is contiguous; used by the global gather and by the exact routine.
 void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B, void **Bpack,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad)
 {
     *Bpack = nullptr; *ATpack = nullptr; *Bbytes = 0; *ATbytes = 0;
     const Variant *v = find_variant(m, n, storage);
     if (!v) return;
+    const Geometry &G = v->geo;
     const int MP = v->mp, half = MP / 2;
     const int epl = storage == 1 ? 8 : 1;                  // k-slots per lane per MFMA
     const int ks = half / epl;
     const int tiles = row_tiles_for(*v, K);
+    const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t esz = storage == 1 ? 2 : 4;
     *m_pad = MP; *n_pad = n;
-    *Bbytes = (size_t)tiles * 32 * MP * esz;
+    *Bbytes = (size_t)nstages * G.rec_bytes;
     *ATbytes = (size_t)K * n * MP * esz;
     unsigned char *pb = (unsigned char *)calloc(*Bbytes, 1);
     unsigned char *pa = (unsigned char *)calloc(*ATbytes, 1);
@@ -551,7 +619,9 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
             memcpy(base + idx * 4, &val, 4);
         }
     };
-    for (int tile = 0; tile < tiles; ++tile)
+    for (int tile = 0; tile < tiles; ++tile) {
+        unsigned char *tb = pb + (size_t)(tile / v->stage_tiles) * G.rec_bytes +
+                            (size_t)(tile % v->stage_tiles) * G.tile_bytes;
         for (int s = 0; s < ks; ++s)
             for (int lane = 0; lane < 64; ++lane) {
                 const int hh = lane / 32, row = tile * 32 + lane % 32;
@@ -559,9 +629,21 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
                 for (int e = 0; e < epl; ++e) {
                     const int i = hh * half + epl * s + e;
                     const float val = (t < K && i < m) ? B[((size_t)t * m + i) * n + j] : 0.0f;
-                    put(pb, (((size_t)tile * ks + s) * 64 + lane) * epl + e, val);
+                    put(tb, ((size_t)s * 64 + lane) * epl + e, val);
                 }
             }
+    }
+    if (v->at_lds)
+        for (int st = 0; st < nstages; ++st) {
+            unsigned char *ab = pb + (size_t)st * G.rec_bytes + (size_t)v->stage_tiles * G.tile_bytes;
+            for (int q = 0; q < G.ts; ++q) {
+                const int t = st * G.ts + q;
+                if (t >= K) break;
+                for (int j = 0; j < n; ++j)
+                    for (int i = 0; i < m; ++i)
+                        put(ab, ((size_t)q * n + j) * G.ats + i, A[((size_t)t * m + i) * n + j]);
+            }
+        }
     for (int t = 0; t < K; ++t)
         for (int j = 0; j < n; ++j)
             for (int i = 0; i < m; ++i)
