@@ -30,8 +30,9 @@
  *     memory on the game's device (e.g. torch.Tensor.data_ptr()).
  *   - Matrices A and B are host, row-major [K][m][n]; they are copied and repacked at
  *     create and the caller keeps ownership.  Candidates are device, row-major
- *     [count][m] fp32, borrowed for the duration of the call (until the stream has run
- *     the enqueued work, for the asynchronous calls).  Rows are NOT checked to lie on
+ *     [count][m] fp32 (4-byte aligned; 16-byte aligned when m is a multiple of 4, so that
+ *     any row of an aligned buffer qualifies), borrowed for the duration of the call (until
+ *     the stream has run the enqueued work, for the asynchronous calls).  Rows are NOT checked to lie on
  *     the simplex: the sweep is defined for any finite x.  Non-finite candidates give
  *     an unspecified result (never a fault).
  *   - Every function returns a bsse_status.  Arguments are validated before any HIP

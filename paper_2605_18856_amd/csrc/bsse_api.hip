@@ -468,6 +468,9 @@ static bsse_status resolve_candidates(bsse_game *g, const float **X, int64_t *co
         *count = g->gen_count;
     }
     if (*count > CHUNK_MAX) return fail(BSSE_EOVERFLOW, "count exceeds 2^31 rows per call");
+    const uintptr_t need = (g->m % 4 == 0) ? 15 : 3;      // whole rows of 16 bytes keep 16-byte alignment
+    if (((uintptr_t)*X & need) != 0)
+        return fail(BSSE_EINVAL, "candidates must be %d-byte aligned", (int)need + 1);
     return BSSE_OK;
 }
 

@@ -56,6 +56,13 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
                void **Bpack, size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad,
                int *n_pad);
 
+// Small-game matrix-core kernel (n = 8, m = 8, K in {4, 8, 12, 16}, fp32); part of the MFMA path.
+bool small_supported(int m, int n, int K, int storage);
+long long small_num_blocks(long long count);
+hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s);
+void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
+                void **ATpack, size_t *ATbytes);
+
 hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
                                const float *X, long long index_base, int m, RunningBest *run,
                                float *best_x, hipStream_t s);

@@ -23,17 +23,15 @@
 // an exact routine for that type, which recomputes the same MFMA tiles (bit-identical) and
 // walks the exact maximisers in ascending action order comparing leader payoffs.
 #include "bsse_internal.h"
+#include "mfma_device.h"
 #include <limits.h>
 #include <stdlib.h>
 #include <string.h>
-#include <type_traits>
 
 namespace bsse {
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -69,14 +67,19 @@ template <int MP> struct Path<float, MP> {
         for (int e = 0; e < HALF; ++e) x[e] = v[e];
     }
     // sum over this lane's half of x[i] * col[i]; col points at the lane's half of the column
-    __device__ static __forceinline__ float half_dot(const xreg *x, const void *col)
+    template <typename BP>      // BP: byte pointer, global (generic) or LDS address space
+    __device__ static __forceinline__ float half_dot(const xreg *x, BP col)
     {
-        const float *c = (const float *)col;
+        typedef typename std::conditional<std::is_same<BP, const lds_byte *>::value,
+                                          const __attribute__((address_space(3))) float *, const float *>::type FP;
+        typedef typename std::conditional<std::is_same<BP, const lds_byte *>::value,
+                                          const __attribute__((address_space(3))) f32x4 *, const f32x4 *>::type VP;
+        const FP c = (FP)col;
         float l = 0.0f;
         if constexpr (HALF % 4 == 0) {
 #pragma unroll
             for (int e = 0; e < HALF; e += 4) {
-                const f32x4 v = *(const f32x4 *)(c + e);
+                const f32x4 v = *(VP)(c + e);
                 l = fmaf(x[e], v[0], l); l = fmaf(x[e + 1], v[1], l);
                 l = fmaf(x[e + 2], v[2], l); l = fmaf(x[e + 3], v[3], l);
             }
@@ -109,80 +112,28 @@ template <int MP> struct Path<__bf16, MP> {
         for (int e = 0; e < HALF; e += 2)
             x[e / 2] = bf16_bits_rne(v[e]) | (bf16_bits_rne(v[e + 1]) << 16);
     }
-    __device__ static __forceinline__ float half_dot(const xreg *x, const void *col)
+    template <typename BP>
+    __device__ static __forceinline__ float half_dot(const xreg *x, BP col)
     {
-        // HIP's uint4 (a struct), not an ext_vector: bit-casting an element extracted from a
-        // clang vector to a bf16 pair was seen to reuse element 0 for all four lanes of the load
-        const uint4 *c = (const uint4 *)col;
+        // l += x.lo*c.lo + x.hi*c.hi on packed bf16 pairs, fp32 accumulate.  Issued as asm on
+        // plain 32-bit words: going through the bf16-pair builtin, a bit-cast of an element
+        // extracted from a clang vector was seen to reuse element 0 for all four words of a load.
+        typedef typename std::conditional<std::is_same<BP, const lds_byte *>::value,
+                                          const __attribute__((address_space(3))) u32x4 *, const u32x4 *>::type VP;
+        const VP c = (VP)col;
         float l = 0.0f;
 #pragma unroll
         for (int e = 0; e < XREGS; e += 4) {
-            const uint4 v = c[e / 4];
-            l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x[e]),
-                                                __builtin_bit_cast(bf16x2, v.x), l, false);
-            l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x[e + 1]),
-                                                __builtin_bit_cast(bf16x2, v.y), l, false);
-            l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x[e + 2]),
-                                                __builtin_bit_cast(bf16x2, v.z), l, false);
-            l = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x[e + 3]),
-                                                __builtin_bit_cast(bf16x2, v.w), l, false);
+            const u32x4 v = c[e / 4];
+            const unsigned w0 = v[0], w1 = v[1], w2 = v[2], w3 = v[3];
+            asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(x[e]), "v"(w0));
+            asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(x[e + 1]), "v"(w1));
+            asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(x[e + 2]), "v"(w2));
+            asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(x[e + 3]), "v"(w3));
         }
         return l;
     }
 };
-
-// Row of a 32x32 accumulator tile held in register r, without the lane-half term 4*(lane/32).
-__device__ __host__ constexpr int acc_row_base(int r) { return 8 * (r / 4) + (r % 4); }
-
-// Partner-lane helpers built on v_permlane32_swap: the two results hold, in every lane, the
-// value of the lane with the same column in the lower half and in the upper half, so any
-// commutative combination of them is the pair's result, identical in both lanes.
-__device__ __forceinline__ float pair_max(float v)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ int pair_min(int v)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
-    return min((int)r[0], (int)r[1]);
-}
-__device__ __forceinline__ float pair_sum(float v)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// Compile-time loop: f(integral_constant<int, I>) for I = Begin, Begin+Step, ... (Step may be
-// negative), so that loop indices can feed immediate operands.
-template <int I, int End, int Step, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr ((Step > 0 && I < End) || (Step < 0 && I > End)) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + Step, End, Step>(f);
-    }
-}
-
-// One step of the "which register holds the maximum" pass, pinned to four instructions:
-//   vcc  = (u != gmax)                      v_cmp_neq_f32
-//   idx  = vcc ? idx : JC                   v_cndmask_b32   (JC is an inline constant, 0..64:
-//                                           a literal would be a second constant-bus read)
-//   hits += number of lanes with u == gmax  s_bcnt0_i32_b64 + s_add_i32 (scalar unit)
-// Written as one asm block so that the 64-bit compare mask lives only in vcc; left to the
-// scheduler, the masks of many steps were kept alive at once and spilled.
-template <int JC>
-__device__ __forceinline__ void match_step(float u, float gmax, int &idx, int &hits)
-{
-    static_assert(JC >= 0 && JC <= 64, "must be an inline constant");
-    int tmp;
-    asm("v_cmp_neq_f32 vcc, %3, %4\n\t"
-        "v_cndmask_b32 %0, %5, %0, vcc\n\t"
-        "s_bcnt0_i32_b64 %2, vcc\n\t"
-        "s_add_i32 %1, %1, %2"
-        : "+v"(idx), "+s"(hits), "=&s"(tmp)
-        : "v"(u), "v"(gmax), "i"(JC)
-        : "vcc", "scc");
-}
 
 // ------------------------------------------------------------------------------------------
 // Stage records.  The packed follower payoffs are cut into "stages" of STAGE_TILES 32-row
@@ -249,7 +200,8 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     __shared__ float red_v[WAVES];
     __shared__ long long red_i[WAVES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, col = lane & 31;
     const int m = g.m, K = g.K;
     const unsigned char *records = reinterpret_cast<const unsigned char *>(g.Bpack);
@@ -366,7 +318,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         }
     };
     // per-type epilogue of a finished group; at_lds = LDS rows of the group's first type
-    auto epilogue = [&](int group, const unsigned char *at_lds) __attribute__((always_inline)) {
+    auto epilogue = [&](int group, const lds_byte *at_lds) __attribute__((always_inline)) {
         static_for<0, TYPES, 1>([&](auto tic) {
             constexpr int ti = decltype(tic)::value;
             const int t = group * TYPES + ti;
@@ -387,9 +339,9 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                     for (int r = 0; r < 16; ++r) {
                         if (N < 32 && acc_row_base(r) / N != ti) continue;
                         pend[np++] = acc[ct][tt][r];
-                        if (np == 2) { pm = fmaxf(fmaxf(pm, pend[0]), pend[1]); np = 0; }
+                        if (np == 2) { pm = vmax3(pm, pend[0], pend[1]); np = 0; }
                     }
-                if (np == 1) pm = fmaxf(pm, pend[0]);
+                if (np == 1) pm = vmax2(pm, pend[0]);
                 const float gm = pair_max(pm);
                 // lowest maximising action of this lane; hits counted over the wavefront
                 int idx = NO_ACTION;
@@ -416,7 +368,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 if (clean[ct]) {
                     float part;
                     if constexpr (AT_LDS)
-                        part = P::half_dot(x[ct], at_lds + ((size_t)(ti * N + js) * G.ats + h * HALF) * sizeof(T));
+                        part = P::half_dot(x[ct], at_lds + (unsigned)(((ti * N + js) * G.ats + h * HALF) * sizeof(T)));
                     else
                         part = P::half_dot(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
                     l = pair_sum(part);
@@ -448,7 +400,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 zero_acc();
 #pragma unroll
                 for (int tt = 0; tt < TPG; ++tt) mfma_tile(tiles + (size_t)(gi * TPG + tt) * TILE_FRAGS, tt);
-                epilogue(g0 + gi, buf + STAGE_TILES * G.tile_bytes + (size_t)gi * TYPES * N * G.ats * sizeof(T));
+                epilogue(g0 + gi, (const lds_byte *)buf + (unsigned)(STAGE_TILES * G.tile_bytes + gi * TYPES * N * G.ats * sizeof(T)));
             }
             stage_sync();
         }
@@ -554,10 +506,14 @@ int row_tiles_for(const Variant &v, int K)
 
 }  // namespace
 
-bool mfma_supported(int m, int n, int K, int storage) { return find_variant(m, n, storage) != nullptr; }
+bool mfma_supported(int m, int n, int K, int storage)
+{
+    return small_supported(m, n, K, storage) || find_variant(m, n, storage) != nullptr;
+}
 
 long long mfma_num_blocks(const GameView &g, PathKind kind, long long count)
 {
+    if (small_supported(g.m, g.n, g.K, kind == PATH_MFMA_BF16 ? 1 : 0)) return small_num_blocks(count);
     const Variant *v = find_variant(g.m, g.n, kind == PATH_MFMA_BF16 ? 1 : 0);
     const long long per = (long long)v->nt * 32 * v->waves;
     return (count + per - 1) / per;
@@ -567,6 +523,7 @@ hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &
                              hipStream_t s)
 {
     if (a.count <= 0) return hipSuccess;
+    if (small_supported(g.m, g.n, g.K, kind == PATH_MFMA_BF16 ? 1 : 0)) return launch_sweep_small(g, a, s);
     const Variant *v = find_variant(g.m, g.n, kind == PATH_MFMA_BF16 ? 1 : 0);
     if (!v) return hipErrorNotSupported;
     const long long blocks = mfma_num_blocks(g, kind, a.count);
@@ -594,6 +551,11 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad)
 {
     *Bpack = nullptr; *ATpack = nullptr; *Bbytes = 0; *ATbytes = 0;
+    if (small_supported(m, n, K, storage)) {
+        *m_pad = 8; *n_pad = n;
+        small_pack(m, n, K, A, B, Bpack, Bbytes, ATpack, ATbytes);
+        return;
+    }
     const Variant *v = find_variant(m, n, storage);
     if (!v) return;
     const Geometry &G = v->geo;

@@ -1,0 +1,263 @@
+// Fused sweep for small games (n = 8 follower actions, m = 8 leader actions, K a multiple of
+// 4 up to 16 types, fp32): steps 2-5 in one persistent kernel that is bound by reading the
+// candidate rows (32 bytes each) once.
+//
+// Matrix-core layout.  One 32x32x2 fp32 MFMA tile holds four types x eight actions as its 32
+// rows and 32 candidates as its columns; four MFMAs (k = m = 8) finish it.  The rows are
+// ordered on the host so that the 16 rows a lane receives (accumulator rows 8q + 4h + rr in
+// register 4q + rr, h = lane/32) are the eight actions of two whole types, 2h and 2h + 1 of
+// the tile: register r holds action r % 8 of the lane's type r / 8.  Each lane therefore
+// finishes (candidate, type) pairs on its own -- maximum, lowest maximising action, leader
+// payoff -- with no cross-lane traffic; the two lane halves of a candidate cover different
+// types and their partial leader values are added once at the end.  The whole follower
+// matrix of the game is 4 registers per tile and lives in registers for the kernel's life;
+// the leader matrix sits in LDS, one padded row per (type, action).
+#include "bsse_internal.h"
+#include "mfma_device.h"
+#include <limits.h>
+#include <stdlib.h>
+#include <string.h>
+
+namespace bsse {
+
+namespace {
+
+constexpr int SM_M = 8, SM_N = 8;
+constexpr int SM_WAVES = 4;
+constexpr int SM_NT = 2;               // 32-candidate tiles per wavefront per iteration
+constexpr int SM_AT_STRIDE = 12;       // floats per leader row in LDS (8 + pad: bank spread)
+constexpr int SM_MAX_TILES = 4;
+
+// TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
+// Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).
+template <int TILES, bool EVAL>
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
+sweep_small_kernel(GameView g, SweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float at_lds[TILES * 4 * SM_N * SM_AT_STRIDE];
+    __shared__ float red_v[SM_WAVES];
+    __shared__ unsigned red_c[SM_WAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, col = lane & 31;
+    const int K = g.K;
+    const unsigned count = (unsigned)a.count;            // <= 2^31 per launch
+
+    const unsigned per_iter = SM_NT * 32;
+    const unsigned n_tasks = (count + per_iter - 1) / per_iter;
+    const unsigned task0 = blockIdx.x * SM_WAVES + wave;
+    const unsigned task_stride = gridDim.x * SM_WAVES;
+
+    // candidate rows of one task: own = x[4h..4h+3] (the MFMA k-slots of this lane half),
+    // oth = the other four components (needed for the leader payoff only)
+    f32x4 own[SM_NT], oth[SM_NT];
+    auto load_task = [&](unsigned task) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) {
+            const unsigned c = task * per_iter + ct * 32 + col;
+            const bool ok = c < count;
+            const float *row = a.X + (size_t)(ok ? c : 0) * SM_M;
+            own[ct] = *(const f32x4 *)(row + 4 * h);
+            oth[ct] = *(const f32x4 *)(row + 4 * (1 - h));
+            if (!ok) { own[ct] = f32x4{ 0, 0, 0, 0 }; oth[ct] = f32x4{ 0, 0, 0, 0 }; }
+        }
+    };
+    if (task0 < n_tasks) load_task(task0);              // first rows in flight during set-up
+
+    // leader rows -> LDS (packed on the host with the padded stride); follower fragments and
+    // priors -> registers
+    {
+        const float *src = reinterpret_cast<const float *>(g.ATpack);
+        for (int e = tid; e < TILES * 4 * SM_N * SM_AT_STRIDE; e += SM_WAVES * 64) at_lds[e] = src[e];
+    }
+    float bfrag[TILES][4];
+    float prior[TILES][2];
+    const lds_float *rows_a[TILES][2];  // this lane's (type) leader rows, own-half columns
+    int oth_delta;                      // float offset from own-half to other-half columns
+    const lds_float *at_l = (const lds_float *)at_lds;
+    {
+        const float *src = reinterpret_cast<const float *>(g.Bpack);
+#pragma unroll
+        for (int T = 0; T < TILES; ++T) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) bfrag[T][s] = src[(T * 4 + s) * 64 + lane];
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl) {
+                const int t = 4 * T + 2 * h + tl;
+                prior[T][tl] = g.prior[t];
+                rows_a[T][tl] = at_l + t * SM_N * SM_AT_STRIDE + 4 * h;
+            }
+        }
+        oth_delta = 4 * (1 - h) - 4 * h;
+    }
+    __syncthreads();
+
+    float best_v = -INFINITY;
+    unsigned best_c = 0xFFFFFFFFu;
+    unsigned tie_count = 0;
+
+#pragma unroll 1
+    for (unsigned task = task0; task < n_tasks; task += task_stride) {
+        f32x4 xo[SM_NT], xt[SM_NT];
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) { xo[ct] = own[ct]; xt[ct] = oth[ct]; }
+        if (task + task_stride < n_tasks) load_task(task + task_stride);   // next rows in flight
+
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) {
+            const unsigned c = task * per_iter + ct * 32 + col;
+            const bool ok = c < count;
+            const bool all_ok = (task * per_iter + ct * 32 + 32) <= count;     // wave-uniform
+            float vhalf = 0.0f;
+#pragma unroll
+            for (int T = 0; T < TILES; ++T) {
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc, 0, 0, 0);
+                static_for<0, 2, 1>([&](auto tlc) {
+                    constexpr int tl = decltype(tlc)::value;
+                    float gm = vmax3(acc[8 * tl], acc[8 * tl + 1], acc[8 * tl + 2]);
+                    gm = vmax3(gm, acc[8 * tl + 3], acc[8 * tl + 4]);
+                    gm = vmax3(gm, acc[8 * tl + 5], acc[8 * tl + 6]);
+                    gm = vmax2(gm, acc[8 * tl + 7]);
+                    int idx = 0, hits = 0;
+                    static_for<7, -1, -1>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        match_step<j>(acc[8 * tl + j], gm, idx, hits);
+                    });
+                    auto leader = [&](int j) __attribute__((always_inline)) {
+                        const lds_float *ra = rows_a[T][tl] + j * SM_AT_STRIDE;
+                        const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
+                        const f32x4 qb = *(const __attribute__((address_space(3))) f32x4 *)(ra + oth_delta);
+                        float l = xo[ct][0] * qa[0];
+                        l = fmaf(xo[ct][1], qa[1], l); l = fmaf(xo[ct][2], qa[2], l);
+                        l = fmaf(xo[ct][3], qa[3], l); l = fmaf(xt[ct][0], qb[0], l);
+                        l = fmaf(xt[ct][1], qb[1], l); l = fmaf(xt[ct][2], qb[2], l);
+                        l = fmaf(xt[ct][3], qb[3], l);
+                        return l;
+                    };
+                    float l;
+                    if (hits == 64 && all_ok) {                       // wave-uniform
+                        l = leader(idx);
+                    } else {
+                        // exact: maximisers in ascending action order, leader payoff decides,
+                        // then the lower action (lane-local; every lane owns its pair)
+                        float lbest = 0.0f;
+                        int jbest = 0, nm = 0;
+#pragma unroll
+                        for (int j = 0; j < SM_N; ++j)
+                            if (acc[8 * tl + j] == gm) {
+                                const float lj = leader(j);
+                                if (nm == 0 || lj > lbest) { lbest = lj; jbest = j; }
+                                ++nm;
+                            }
+                        l = lbest; idx = jbest;
+                        tie_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok && nm >= 2));
+                    }
+                    vhalf = fmaf(prior[T][tl], l, vhalf);
+                    if (EVAL && a.br_out && ok) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx;
+                });
+            }
+            float v = pair_sum(vhalf);
+            if (!(v == v)) v = -INFINITY;
+            if (EVAL) {
+                if (a.V_out && ok && h == 0) a.V_out[c] = v;
+            } else if (ok && v > best_v) {           // a lane meets its candidates in ascending order
+                best_v = v; best_c = c;
+            }
+        }
+    }
+
+    if (!EVAL) {
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) {          // both lane halves hold the same values
+            const float ov = __shfl_xor(best_v, d, 64);
+            const unsigned oc = __shfl_xor(best_c, d, 64);
+            if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; }
+        }
+        if (lane == 0) { red_v[wave] = best_v; red_c[wave] = best_c; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < SM_WAVES; ++w)
+                if (red_v[w] > best_v || (red_v[w] == best_v && red_c[w] < best_c)) {
+                    best_v = red_v[w]; best_c = red_c[w];
+                }
+            a.blk_v[blockIdx.x] = best_v;
+            a.blk_i[blockIdx.x] = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
+        }
+        if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
+    }
+}
+
+typedef void (*small_kernel_t)(GameView, SweepArgs);
+small_kernel_t small_kernel_for(int K, bool eval)
+{
+    switch (K / 4) {
+    case 1: return eval ? sweep_small_kernel<1, true> : sweep_small_kernel<1, false>;
+    case 2: return eval ? sweep_small_kernel<2, true> : sweep_small_kernel<2, false>;
+    case 3: return eval ? sweep_small_kernel<3, true> : sweep_small_kernel<3, false>;
+    case 4: return eval ? sweep_small_kernel<4, true> : sweep_small_kernel<4, false>;
+    }
+    return nullptr;
+}
+
+}  // namespace
+
+bool small_supported(int m, int n, int K, int storage)
+{
+    return storage == 0 && n == SM_N && m == SM_M && K % 4 == 0 && K / 4 >= 1 && K / 4 <= SM_MAX_TILES;
+}
+
+// Persistent grid: one resident set of workgroups (4 per compute unit), never more than the work.
+long long small_num_blocks(long long count)
+{
+    const long long per_wg = (long long)SM_WAVES * SM_NT * 32;
+    const long long need = (count + per_wg - 1) / per_wg;
+    const long long cap = 256 * 4;
+    return need < cap ? need : cap;
+}
+
+hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s)
+{
+    if (a.count <= 0) return hipSuccess;
+    small_kernel_t k = small_kernel_for(g.K, a.blk_v == nullptr);
+    if (!k) return hipErrorNotSupported;
+    if (((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
+    hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
+    return hipGetLastError();
+}
+
+// Host packing for the small-game kernel.
+// Bpack: [tile][k-step s][lane] fp32; lane = 32*kh + i supplies B_t[k = 4*kh + s][j] for tile
+// row i = 8q + 4hh + rr, which stands for type t = 4*tile + 2*hh + q/2, action j = 4*(q%2) + rr.
+// ATpack: [type][action][12] fp32: the leader column of (type, action) over the m leader
+// actions, zero padded to 8, then 4 floats of padding.
+void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
+                void **ATpack, size_t *ATbytes)
+{
+    const int tiles = K / 4;
+    *Bbytes = (size_t)tiles * 4 * 64 * sizeof(float);
+    *ATbytes = (size_t)K * SM_N * SM_AT_STRIDE * sizeof(float);
+    float *pb = (float *)calloc(*Bbytes, 1);
+    float *pa = (float *)calloc(*ATbytes, 1);
+    *Bpack = pb; *ATpack = pa;
+    if (!pb || !pa) { free(pb); free(pa); *Bpack = nullptr; *ATpack = nullptr; return; }
+    for (int T = 0; T < tiles; ++T)
+        for (int s = 0; s < 4; ++s)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int kh = lane / 32, i = lane % 32;
+                const int q = i / 8, hh = (i % 8) / 4, rr = i % 4;
+                const int t = 4 * T + 2 * hh + q / 2, j = 4 * (q % 2) + rr, k = 4 * kh + s;
+                pb[(T * 4 + s) * 64 + lane] = k < m ? B[((size_t)t * m + k) * n + j] : 0.0f;
+            }
+    for (int t = 0; t < K; ++t)
+        for (int j = 0; j < n; ++j)
+            for (int i = 0; i < m; ++i)
+                pa[((size_t)t * SM_N + j) * SM_AT_STRIDE + i] = A[((size_t)t * m + i) * n + j];
+}
+
+}  // namespace bsse

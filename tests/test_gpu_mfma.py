@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 # and of the type count
 MFMA_SHAPES = [
     (8, 8, 4, "f32"), (8, 8, 3, "f32"), (5, 8, 9, "f32"),
+    (8, 8, 8, "f32"), (6, 8, 12, "f32"), (8, 8, 16, "f32"), (3, 8, 4, "f32"),
     (16, 16, 3, "f32"), (12, 16, 2, "f32"),
     (32, 32, 16, "f32"), (20, 32, 5, "f32"),
     (32, 64, 3, "f32"), (24, 64, 2, "f32"),
@@ -25,7 +26,7 @@ MFMA_SHAPES = [
 
 
 @pytest.mark.parametrize("shape", MFMA_SHAPES, ids=lambda s: "m%dn%dK%d%s" % s)
-@pytest.mark.parametrize("count", [1, 33, 1300])
+@pytest.mark.parametrize("count", [1, 33, 1300, 70001])
 def test_mfma_path_parity(shape, count):
     m, n, K, storage = shape
     game = workloads.small_game(m, n, K, 500 + m + n + K, kind="normal", storage=storage)
@@ -33,7 +34,7 @@ def test_mfma_path_parity(shape, count):
     _full_check(game, X, bsse.BSSE_PATH_MFMA, "mfma")
 
 
-@pytest.mark.parametrize("shape", [(8, 8, 5, "f32"), (16, 16, 3, "f32"), (32, 32, 3, "f32"),
+@pytest.mark.parametrize("shape", [(8, 8, 5, "f32"), (8, 8, 4, "f32"), (7, 8, 8, "f32"), (16, 16, 3, "f32"), (32, 32, 3, "f32"),
                                    (32, 64, 2, "f32"), (16, 32, 3, "bf16"), (64, 128, 2, "bf16")],
                          ids=lambda s: "m%dn%dK%d%s" % s)
 @pytest.mark.parametrize("kind", ["dyadic", "vertex"])
