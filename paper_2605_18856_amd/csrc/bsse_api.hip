@@ -50,10 +50,9 @@ extern "C" const char *bsse_status_name(bsse_status s)
     } while (0)
 
 // ------------------------------------------------------------------------------ handle
-struct HostOut {            // pinned; filled by device-to-host copies in bsse_sweep_result
-    RunningBest run;
-    unsigned long long ties;
-    float fin_v;
+struct HostOut {            // pinned, device-visible: kernels write results here directly
+    RunningBest run;        // by the merge kernel of every chunk
+    float fin_v;            // by the one-row re-evaluation of the winner
 };
 
 struct bsse_game {
@@ -75,12 +74,11 @@ struct bsse_game {
     RunningBest *run = nullptr;
     float *best_x = nullptr;
     unsigned long long *tie_counter = nullptr;
-    float *fin_v = nullptr;
-    int32_t *fin_br = nullptr;
     // pinned host
     HostOut *h_out = nullptr;
     int32_t *h_br = nullptr;
     long long n_evals = 0;
+    bool fresh = true;       // the next chunk starts a new sweep
     // kernel timing
     bool timing = false;
     std::vector<hipEvent_t> ev;      // start/stop pairs of recorded launches
@@ -139,7 +137,6 @@ void free_game(bsse_game *g)
     (void)hipFree(g->gen); (void)hipFree(g->lat_table);
     (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
-    (void)hipFree(g->fin_v); (void)hipFree(g->fin_br);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -313,8 +310,6 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->fin_v, 4)) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->fin_br, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
         if (e != hipSuccess) { st = fail(BSSE_ENOMEM, "hipHostMalloc: %s", hipGetErrorString(e)); break; }
@@ -450,7 +445,7 @@ extern "C" bsse_status bsse_sweep_reset(bsse_game *g)
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
     DeviceGuard dg(g->device);
     if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
-    HIP_TRY(launch_reset(g->run, g->tie_counter, g->stream));
+    g->fresh = true;          // consumed by the merge kernel of the next chunk: no launch here
     g->n_evals = 0;
     return BSSE_OK;
 }
@@ -504,7 +499,9 @@ extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_de
     }
     HIP_TRY(le);
     HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, candidates_dev, index_base, g->m,
-                                g->run, g->best_x, g->stream));
+                                g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
+                                g->stream));
+    g->fresh = false;
     g->n_evals += (long long)count * g->K;
     return BSSE_OK;
 }
@@ -516,15 +513,17 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     if (!res) return fail(BSSE_EINVAL, "res is NULL");
     DeviceGuard dg(g->device);
     if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
-    // best responses of the winner: the same kernel, one row, per-candidate outputs on
+    if (g->fresh) {                        // nothing swept since the last reset
+        HIP_TRY(hipStreamSynchronize(g->stream));
+        res->best_value = 0.0; res->best_index = -1; res->n_evals = 0; res->n_tie_evals = 0;
+        return BSSE_OK;
+    }
+    // best responses of the winner: the same kernel, one row, per-candidate outputs written
+    // straight into pinned host memory
     SweepArgs a{};
     a.X = g->best_x; a.count = 1; a.index_base = 0;
-    a.V_out = g->fin_v; a.br_out = g->fin_br;
+    a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
     HIP_TRY(launch_sweep(g, a, true));
-    HIP_TRY(hipMemcpyAsync(&g->h_out->run, g->run, sizeof(RunningBest), hipMemcpyDeviceToHost, g->stream));
-    HIP_TRY(hipMemcpyAsync(&g->h_out->ties, g->tie_counter, 8, hipMemcpyDeviceToHost, g->stream));
-    HIP_TRY(hipMemcpyAsync(&g->h_out->fin_v, g->fin_v, 4, hipMemcpyDeviceToHost, g->stream));
-    HIP_TRY(hipMemcpyAsync(g->h_br, g->fin_br, (size_t)g->K * 4, hipMemcpyDeviceToHost, g->stream));
     HIP_TRY(hipStreamSynchronize(g->stream));
     const bool has = g->h_out->run.has != 0;
     if (has && !(g->h_out->fin_v == g->h_out->run.value))
@@ -533,7 +532,7 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     res->best_value = has ? (double)g->h_out->run.value : 0.0;
     res->best_index = has ? (int64_t)g->h_out->run.index : -1;
     res->n_evals = g->n_evals;
-    res->n_tie_evals = (int64_t)g->h_out->ties;
+    res->n_tie_evals = (int64_t)g->h_out->run.ties;
     if (has && best_response_out) memcpy(best_response_out, g->h_br, (size_t)g->K * 4);
     return BSSE_OK;
 }

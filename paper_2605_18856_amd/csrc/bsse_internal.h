@@ -38,6 +38,7 @@ struct RunningBest {
     float value;
     int   has;               // 0 until a chunk has been merged
     long long index;
+    unsigned long long ties; // tie evaluations of all merged chunks
 };
 
 enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3 };
@@ -63,11 +64,13 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes);
 
+// first != 0: the running best is replaced, not merged (start of a sweep).  tie_counter (the
+// chunk's count, left by the sweep kernel) is folded into run->ties and cleared.  The merged
+// record is also written to run_host (device-visible pinned host memory).
 hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
-                               const float *X, long long index_base, int m, RunningBest *run,
-                               float *best_x, hipStream_t s);
-
-hipError_t launch_reset(RunningBest *run, unsigned long long *tie_counter, hipStream_t s);
+                               const float *X, long long index_base, int m, int first,
+                               unsigned long long *tie_counter, RunningBest *run,
+                               RunningBest *run_host, float *best_x, hipStream_t s);
 
 hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
                           float *out, hipStream_t s);

@@ -21,7 +21,8 @@ __device__ __forceinline__ bool better(float v, long long i, float bv, long long
 __global__ void __launch_bounds__(RT)
 reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict__ blk_i,
                     long long nblocks, const float *__restrict__ X, long long index_base, int m,
-                    RunningBest *run, float *best_x)
+                    int first, unsigned long long *tie_counter, RunningBest *run,
+                    RunningBest *run_host, float *best_x)
 {
     __shared__ float sv[RT / 64];
     __shared__ long long si[RT / 64];
@@ -47,12 +48,18 @@ reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict
         for (int w = 1; w < RT / 64; ++w)
             if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
         long long w_row = -1;
-        if (bi != LLONG_MAX && (!run->has || bv > run->value)) {
-            run->value = bv;
-            run->index = bi;
-            run->has = 1;
+        RunningBest r = *run;
+        if (first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
+        if (bi != LLONG_MAX && (!r.has || bv > r.value)) {
+            r.value = bv;
+            r.index = bi;
+            r.has = 1;
             w_row = bi - index_base;
         }
+        r.ties += *tie_counter;
+        *tie_counter = 0ull;                 // the next chunk starts from zero
+        *run = r;
+        *run_host = r;
         win = w_row;
     }
     __syncthreads();
@@ -61,31 +68,16 @@ reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict
         for (int i = threadIdx.x; i < m; i += RT) best_x[i] = X[row * m + i];
 }
 
-__global__ void reset_kernel(RunningBest *run, unsigned long long *tie_counter)
-{
-    run->value = 0.0f;
-    run->has = 0;
-    run->index = -1;
-    *tie_counter = 0ull;
-}
-
 }  // namespace
 
-// Clears the running best and the tie counter with a kernel (not a memset node), so the
-// call can sit inside a captured graph.
-hipError_t launch_reset(RunningBest *run, unsigned long long *tie_counter, hipStream_t s)
-{
-    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, s, run, tie_counter);
-    return hipGetLastError();
-}
-
 hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
-                               const float *X, long long index_base, int m, RunningBest *run,
-                               float *best_x, hipStream_t s)
+                               const float *X, long long index_base, int m, int first,
+                               unsigned long long *tie_counter, RunningBest *run,
+                               RunningBest *run_host, float *best_x, hipStream_t s)
 {
     if (nblocks <= 0) return hipSuccess;
     hipLaunchKernelGGL(reduce_merge_kernel, dim3(1), dim3(RT), 0, s, blk_v, blk_i, nblocks, X,
-                       index_base, m, run, best_x);
+                       index_base, m, first, tie_counter, run, run_host, best_x);
     return hipGetLastError();
 }
 

@@ -104,65 +104,101 @@ sweep_small_kernel(GameView g, SweepArgs a)
         for (int ct = 0; ct < SM_NT; ++ct) { xo[ct] = own[ct]; xt[ct] = oth[ct]; }
         if (task + task_stride < n_tasks) load_task(task + task_stride);   // next rows in flight
 
+        // Both candidate tiles and both of the lane's types advance together through one
+        // straight-line block (four independent dependency chains for the scheduler to
+        // interleave); the exact tie routine is a single rare branch at the end.
+        float vhalf[SM_NT];
+        bool all_ok[SM_NT];
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
-            const unsigned c = task * per_iter + ct * 32 + col;
-            const bool ok = c < count;
-            const bool all_ok = (task * per_iter + ct * 32 + 32) <= count;     // wave-uniform
-            float vhalf = 0.0f;
+            vhalf[ct] = 0.0f;
+            all_ok[ct] = (task * per_iter + ct * 32 + 32) <= count;            // wave-uniform
+        }
 #pragma unroll
-            for (int T = 0; T < TILES; ++T) {
-                f32x16 acc;
+        for (int T = 0; T < TILES; ++T) {
+            f32x16 acc[SM_NT];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            for (int ct = 0; ct < SM_NT; ++ct)
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc, 0, 0, 0);
+                for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int ct = 0; ct < SM_NT; ++ct)
+                    acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc[ct], 0, 0, 0);
+
+            float gm[SM_NT][2], l[SM_NT][2];
+            int idx[SM_NT][2], hits[SM_NT][2];
+            auto leader = [&](int ct, int tl, int j) __attribute__((always_inline)) {
+                const lds_float *ra = rows_a[T][tl] + j * SM_AT_STRIDE;
+                const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
+                const f32x4 qb = *(const __attribute__((address_space(3))) f32x4 *)(ra + oth_delta);
+                float v = xo[ct][0] * qa[0];
+                v = fmaf(xo[ct][1], qa[1], v); v = fmaf(xo[ct][2], qa[2], v);
+                v = fmaf(xo[ct][3], qa[3], v); v = fmaf(xt[ct][0], qb[0], v);
+                v = fmaf(xt[ct][1], qb[1], v); v = fmaf(xt[ct][2], qb[2], v);
+                v = fmaf(xt[ct][3], qb[3], v);
+                return v;
+            };
+            bool dirty = false;                                                   // wave-uniform
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct)
                 static_for<0, 2, 1>([&](auto tlc) {
                     constexpr int tl = decltype(tlc)::value;
-                    float gm = vmax3(acc[8 * tl], acc[8 * tl + 1], acc[8 * tl + 2]);
-                    gm = vmax3(gm, acc[8 * tl + 3], acc[8 * tl + 4]);
-                    gm = vmax3(gm, acc[8 * tl + 5], acc[8 * tl + 6]);
-                    gm = vmax2(gm, acc[8 * tl + 7]);
-                    int idx = 0, hits = 0;
+                    float m3 = vmax3(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2]);
+                    m3 = vmax3(m3, acc[ct][8 * tl + 3], acc[ct][8 * tl + 4]);
+                    m3 = vmax3(m3, acc[ct][8 * tl + 5], acc[ct][8 * tl + 6]);
+                    gm[ct][tl] = vmax2(m3, acc[ct][8 * tl + 7]);
+                    int ix = 0, ht = 0;
                     static_for<7, -1, -1>([&](auto jc) {
                         constexpr int j = decltype(jc)::value;
-                        match_step<j>(acc[8 * tl + j], gm, idx, hits);
+                        match_step<j>(acc[ct][8 * tl + j], gm[ct][tl], ix, ht);
                     });
-                    auto leader = [&](int j) __attribute__((always_inline)) {
-                        const lds_float *ra = rows_a[T][tl] + j * SM_AT_STRIDE;
-                        const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
-                        const f32x4 qb = *(const __attribute__((address_space(3))) f32x4 *)(ra + oth_delta);
-                        float l = xo[ct][0] * qa[0];
-                        l = fmaf(xo[ct][1], qa[1], l); l = fmaf(xo[ct][2], qa[2], l);
-                        l = fmaf(xo[ct][3], qa[3], l); l = fmaf(xt[ct][0], qb[0], l);
-                        l = fmaf(xt[ct][1], qb[1], l); l = fmaf(xt[ct][2], qb[2], l);
-                        l = fmaf(xt[ct][3], qb[3], l);
-                        return l;
-                    };
-                    float l;
-                    if (hits == 64 && all_ok) {                       // wave-uniform
-                        l = leader(idx);
-                    } else {
-                        // exact: maximisers in ascending action order, leader payoff decides,
-                        // then the lower action (lane-local; every lane owns its pair)
+                    idx[ct][tl] = ix; hits[ct][tl] = ht;
+                    dirty = dirty || ht != 64 || !all_ok[ct];
+                });
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct)
+#pragma unroll
+                for (int tl = 0; tl < 2; ++tl) l[ct][tl] = leader(ct, tl, idx[ct][tl]);
+            if (dirty) {
+                // exact: maximisers in ascending action order, leader payoff decides, then the
+                // lower action (lane-local; every lane owns its (candidate, type) pair)
+#pragma unroll
+                for (int ct = 0; ct < SM_NT; ++ct)
+                    static_for<0, 2, 1>([&](auto tlc) {
+                        constexpr int tl = decltype(tlc)::value;
+                        if (hits[ct][tl] == 64 && all_ok[ct]) return;
+                        const bool ok = task * per_iter + ct * 32 + col < count;
                         float lbest = 0.0f;
                         int jbest = 0, nm = 0;
 #pragma unroll
                         for (int j = 0; j < SM_N; ++j)
-                            if (acc[8 * tl + j] == gm) {
-                                const float lj = leader(j);
+                            if (acc[ct][8 * tl + j] == gm[ct][tl]) {
+                                const float lj = leader(ct, tl, j);
                                 if (nm == 0 || lj > lbest) { lbest = lj; jbest = j; }
                                 ++nm;
                             }
-                        l = lbest; idx = jbest;
+                        l[ct][tl] = lbest; idx[ct][tl] = jbest;
                         tie_count += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ok && nm >= 2));
-                    }
-                    vhalf = fmaf(prior[T][tl], l, vhalf);
-                    if (EVAL && a.br_out && ok) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx;
-                });
+                    });
             }
-            float v = pair_sum(vhalf);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct)
+#pragma unroll
+                for (int tl = 0; tl < 2; ++tl) {
+                    vhalf[ct] = fmaf(prior[T][tl], l[ct][tl], vhalf[ct]);
+                    if (EVAL) {
+                        const unsigned c = task * per_iter + ct * 32 + col;
+                        if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx[ct][tl];
+                    }
+                }
+        }
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) {
+            const unsigned c = task * per_iter + ct * 32 + col;
+            const bool ok = c < count;
+            float v = pair_sum(vhalf[ct]);
             if (!(v == v)) v = -INFINITY;
             if (EVAL) {
                 if (a.V_out && ok && h == 0) a.V_out[c] = v;
