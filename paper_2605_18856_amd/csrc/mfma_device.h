@@ -60,25 +60,44 @@ template <int I, int End, int Step, class F> __device__ __forceinline__ void sta
     }
 }
 
-// One step of the "which register holds the maximum" pass, pinned to four instructions:
-//   vcc  = (u != gmax)                      v_cmp_neq_f32
-//   idx  = vcc ? idx : JC                   v_cndmask_b32   (JC is an inline constant, 0..64:
-//                                           a literal would be a second constant-bus read)
-//   hits += number of lanes with u == gmax  s_bcnt0_i32_b64 + s_add_i32 (scalar unit)
-// Written as one asm block so that the 64-bit compare mask lives only in vcc; left to the
-// scheduler, the masks of many steps were kept alive at once and spilled.
-template <int JC>
-__device__ __forceinline__ void match_step(float u, float gmax, int &idx, int &hits)
+// Four steps of the "which register holds the maximum" pass:
+//     sum += sum_k (u_k == gmax ? c_k : 0),   k = 0..3
+// where c_k = (action of register k) + 2^16, so that after all registers sum & 0xFFFF is the
+// maximising action and sum >> 16 the number of maximisers (the action is only meaningful
+// when that number is one; callers send every other case through an exact routine).
+// Ten vector instructions for four values, nothing on the scalar unit.  Written as one asm
+// block for two reasons: the four compare masks live in three scalar pairs plus vcc only
+// inside the block (left to the scheduler, masks of many steps were kept alive and spilled),
+// and every select stands three instructions behind its compare, which satisfies the two wait
+// states this part needs between a vector write of a scalar register and a vector read of it.
+__device__ __forceinline__ void match4(float u0, float u1, float u2, float u3, float gmax,
+                                       unsigned c0, unsigned c1, unsigned c2, unsigned c3,
+                                       unsigned &sum)
 {
-    static_assert(JC >= 0 && JC <= 64, "must be an inline constant");
-    int tmp;
-    asm("v_cmp_neq_f32 vcc, %3, %4\n\t"
-        "v_cndmask_b32 %0, %5, %0, vcc\n\t"
-        "s_bcnt0_i32_b64 %2, vcc\n\t"
-        "s_add_i32 %1, %1, %2"
-        : "+v"(idx), "+s"(hits), "=&s"(tmp)
-        : "v"(u), "v"(gmax), "i"(JC)
-        : "vcc", "scc");
+    unsigned t0, t1, t2, t3;
+    unsigned long long m0, m1, m2;
+    asm("v_cmp_eq_f32 %[m0], %[u0], %[g]\n\t"
+        "v_cmp_eq_f32 %[m1], %[u1], %[g]\n\t"
+        "v_cmp_eq_f32 %[m2], %[u2], %[g]\n\t"
+        "v_cmp_eq_f32 vcc, %[u3], %[g]\n\t"
+        "v_cndmask_b32 %[t0], 0, %[c0], %[m0]\n\t"
+        "v_cndmask_b32 %[t1], 0, %[c1], %[m1]\n\t"
+        "v_cndmask_b32 %[t2], 0, %[c2], %[m2]\n\t"
+        "v_cndmask_b32 %[t3], 0, %[c3], vcc\n\t"
+        "v_add3_u32 %[s], %[s], %[t0], %[t1]\n\t"
+        "v_add3_u32 %[s], %[s], %[t2], %[t3]"
+        : [s] "+v"(sum), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
+          [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2)
+        : [u0] "v"(u0), [u1] "v"(u1), [u2] "v"(u2), [u3] "v"(u3), [g] "v"(gmax),
+          [c0] "v"(c0), [c1] "v"(c1), [c2] "v"(c2), [c3] "v"(c3)
+        : "vcc");
+}
+
+// (a + b) over the two lanes of a candidate, same value in both (integers)
+__device__ __forceinline__ unsigned pair_add_u32(unsigned v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return r[0] + r[1];
 }
 
 }  // namespace bsse

@@ -128,7 +128,8 @@ sweep_small_kernel(GameView g, SweepArgs a)
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc[ct], 0, 0, 0);
 
             float gm[SM_NT][2], l[SM_NT][2];
-            int idx[SM_NT][2], hits[SM_NT][2];
+            int idx[SM_NT][2];
+            bool single[SM_NT][2];      // wave-uniform: every lane has exactly one maximiser
             auto leader = [&](int ct, int tl, int j) __attribute__((always_inline)) {
                 const lds_float *ra = rows_a[T][tl] + j * SM_AT_STRIDE;
                 const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
@@ -149,13 +150,14 @@ sweep_small_kernel(GameView g, SweepArgs a)
                     m3 = vmax3(m3, acc[ct][8 * tl + 3], acc[ct][8 * tl + 4]);
                     m3 = vmax3(m3, acc[ct][8 * tl + 5], acc[ct][8 * tl + 6]);
                     gm[ct][tl] = vmax2(m3, acc[ct][8 * tl + 7]);
-                    int ix = 0, ht = 0;
-                    static_for<7, -1, -1>([&](auto jc) {
-                        constexpr int j = decltype(jc)::value;
-                        match_step<j>(acc[ct][8 * tl + j], gm[ct][tl], ix, ht);
-                    });
-                    idx[ct][tl] = ix; hits[ct][tl] = ht;
-                    dirty = dirty || ht != 64 || !all_ok[ct];
+                    unsigned ms = 0u;            // sum of (action + 2^16) over maximising registers
+                    match4(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2], acc[ct][8 * tl + 3],
+                           gm[ct][tl], 65536u, 65537u, 65538u, 65539u, ms);
+                    match4(acc[ct][8 * tl + 4], acc[ct][8 * tl + 5], acc[ct][8 * tl + 6], acc[ct][8 * tl + 7],
+                           gm[ct][tl], 65540u, 65541u, 65542u, 65543u, ms);
+                    idx[ct][tl] = (int)(ms & 7u);
+                    single[ct][tl] = __builtin_amdgcn_ballot_w64((ms >> 16) != 1u) == 0ull && all_ok[ct];
+                    dirty = dirty || !single[ct][tl];
                 });
 #pragma unroll
             for (int ct = 0; ct < SM_NT; ++ct)
@@ -168,7 +170,7 @@ sweep_small_kernel(GameView g, SweepArgs a)
                 for (int ct = 0; ct < SM_NT; ++ct)
                     static_for<0, 2, 1>([&](auto tlc) {
                         constexpr int tl = decltype(tlc)::value;
-                        if (hits[ct][tl] == 64 && all_ok[ct]) return;
+                        if (single[ct][tl]) return;
                         const bool ok = task * per_iter + ct * 32 + col < count;
                         float lbest = 0.0f;
                         int jbest = 0, nm = 0;
