@@ -21,6 +21,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "valu": 78.6, "valu_bf16": 78.6}
 
+# HBM bytes per launch of the fused sweep kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (profiles/*_traffic.md; FETCH_SIZE reads half of a known-size copy on this part, so it is
+# scaled by 2.0; WRITE_SIZE reads a known-size fill exactly)
+TRAFFIC_BYTES = {
+    "config2": (16449.4 * 2.0 + 64.0) * 1024.0,
+    "config4_chunk": (2 * 386997.0 * 2.0 + 2 * 267.1) * 1024.0,   # the per-dispatch mean mixes sweeps with one-row launches
+}
+
 # workload -> (config number, candidates per step, note)
 WORKLOADS = {
     "config1": (1, None, "m=n=3 K=2 lattice N=100 (5151 candidates)"),
@@ -76,18 +84,21 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
 
     flops = evals * (2.0 * game.m * game.n + 2.0 * game.m)       # algorithmic, per launch
     bytes_ = count * 4.0 * game.m                                  # candidate rows read once
-    ai = flops / bytes_
-    if path.startswith("mfma"):
-        bound, unit, peak = "mfma", "TFLOP/s", PEAK_TFLOPS[path]
-        achieved = flops / (k_ms * 1e-3) / 1e12
-    elif ai > PEAK_TFLOPS["valu"] * 1e12 / (HBM_PEAK_GBS * 1e9):
-        bound, unit, peak = "alu", "TFLOP/s", PEAK_TFLOPS["valu"]
-        achieved = flops / (k_ms * 1e-3) / 1e12
-    else:
+    # the bound is whichever ideal time is longer: bytes at HBM peak or flops at the peak of
+    # the arithmetic unit the path runs on
+    flop_peak = PEAK_TFLOPS[path]
+    t_hbm = bytes_ / (HBM_PEAK_GBS * 1e9)
+    t_flop = flops / (flop_peak * 1e12)
+    if t_hbm >= t_flop:
         bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
         achieved = bytes_ / (k_ms * 1e-3) / 1e9
+    else:
+        bound = "mfma" if path.startswith("mfma") else "alu"
+        unit, peak = "TFLOP/s", flop_peak
+        achieved = flops / (k_ms * 1e-3) / 1e12
     roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None, "kernel": "fused sweep (" + path + ")",
+                "frac": achieved / peak, "traffic": TRAFFIC_BYTES.get(name),
+                "kernel": "fused sweep (" + path + ")",
                 "kernel_ms": k_ms, "launches": launches,
                 "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": bytes_}
 
@@ -110,8 +121,8 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
         c0 = time.perf_counter()
         osweep.sweep(game.A, game.B, game.prior, Xp, per_candidate=False, nthreads=cores)
         per_row = max((time.perf_counter() - c0) / probe, 1e-9)
-        sample = int(min(count, max(probe, 12.0 / per_row)))
-        passes = max(1, int(12.0 / (per_row * sample))) if sample == count else 1
+        sample = int(min(count, max(probe, 15.0 / per_row)))
+        passes = max(1, int(15.0 / (per_row * sample))) if sample == count else 1
         passes = min(passes, 2000)
         Xh = rows(sample)
         c0 = time.perf_counter()
@@ -131,6 +142,32 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     }
 
 
+def large_batch_leg():
+    """Config-2 game, 2^26 candidates (2 GiB, eight times the last-level cache): the sweep
+    kernel alone, HIP-event timed, as achieved HBM bandwidth."""
+    import torch
+    from paper_2605_18856_amd import bsse, workloads
+    game = workloads.game(2)
+    count = 1 << 26
+    g = bsse.bsse_create(game.m, game.n, game.K, game.A, game.B, game.prior)
+    Xd = torch.empty((count, game.m), dtype=torch.float32, device="cuda")
+    bsse.bsse_dirichlet(g, game.candidate_seed, 0, count, Xd)
+    bsse.bsse_sweep_reset(g)
+    bsse.bsse_sweep_chunk(g, Xd, count, 0)
+    bsse.bsse_set_timing(g, True)
+    for _ in range(5):
+        bsse.bsse_sweep_chunk(g, Xd, count, 0)
+    ms, k = bsse.bsse_get_timing(g)
+    out = bsse.bsse_sweep_result(g)
+    g.close()
+    k_ms = ms / k
+    gbs = count * 4.0 * game.m / (k_ms * 1e-3) / 1e9
+    return {"workload": "config2 game, 2^26 candidates per launch", "kernel_ms": k_ms,
+            "evals_per_s": count * game.K / (k_ms * 1e-3), "bound": "hbm", "achieved": gbs,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+            "best_index": out.best_index}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +175,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", action="store_true",
+                    help="time the named workload only (skip the short extra legs on the other "
+                         "configurations and the large-batch leg)")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="also run a plain 256 MiB device copy 5 times (a known-size reference "
+                         "kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -151,6 +194,13 @@ def main():
     default_steps = {"config1": 200, "config2": 200, "config3": 20, "config4_chunk": 3, "config5_sub": 3}
     steps = args.steps if args.steps is not None else default_steps[args.workload]
     warmup = args.warmup if args.warmup is not None else max(1, min(10, steps // 4))
+    if args.copy_reference:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     r = run_workload(args.workload, steps, warmup, not args.no_cpu_baseline)
     game = r["game"]
     line = {
@@ -167,6 +217,21 @@ def main():
         "result": {"best_index": r["best_index"], "best_value": r["best_value"],
                    "n_tie_evals": r["n_tie_evals"]},
     }
+    if not args.only:
+        # short extra legs: the other configurations (not part of `value`), and the sweep
+        # kernel alone on a batch far larger than the caches for the memory-bound game
+        others = {}
+        for w, (st, wu) in {"config1": (50, 5), "config2": (50, 5), "config3": (5, 1),
+                            "config4_chunk": (3, 1), "config5_sub": (3, 1)}.items():
+            if w == args.workload:
+                continue
+            o = run_workload(w, st, wu, False)
+            others[w] = {"value": o["value"], "ms_per_step": o["ms_per_step"], "path": o["path"],
+                         "candidates_per_step": o["count"],
+                         "roofline": {k: o["roofline"][k] for k in
+                                      ("bound", "achieved", "peak", "unit", "frac", "kernel_ms")}}
+        line["other_workloads"] = others
+        line["large_batch_sweep_kernel"] = large_batch_leg()
     print(json.dumps(line), flush=True)
 
 
