@@ -93,6 +93,57 @@ __device__ __forceinline__ void match4(float u0, float u1, float u2, float u3, f
         : "vcc");
 }
 
+// The same for eight values in one asm block, and the running maximum over sixteen values in
+// one block: the compiler pads every boundary between two asm statements with a no-op, so
+// fewer, larger blocks save issue slots in the epilogue.
+__device__ __forceinline__ void match8(const float *u, float gmax, const unsigned *c, unsigned &sum)
+{
+    unsigned t0, t1, t2, t3;
+    unsigned long long m0, m1, m2;
+    asm("v_cmp_eq_f32 %[m0], %[u0], %[g]\n\t"
+        "v_cmp_eq_f32 %[m1], %[u1], %[g]\n\t"
+        "v_cmp_eq_f32 %[m2], %[u2], %[g]\n\t"
+        "v_cmp_eq_f32 vcc, %[u3], %[g]\n\t"
+        "v_cndmask_b32 %[t0], 0, %[c0], %[m0]\n\t"
+        "v_cndmask_b32 %[t1], 0, %[c1], %[m1]\n\t"
+        "v_cndmask_b32 %[t2], 0, %[c2], %[m2]\n\t"
+        "v_cndmask_b32 %[t3], 0, %[c3], vcc\n\t"
+        "v_add3_u32 %[s], %[s], %[t0], %[t1]\n\t"
+        "v_cmp_eq_f32 %[m0], %[u4], %[g]\n\t"
+        "v_cmp_eq_f32 %[m1], %[u5], %[g]\n\t"
+        "v_cmp_eq_f32 %[m2], %[u6], %[g]\n\t"
+        "v_cmp_eq_f32 vcc, %[u7], %[g]\n\t"
+        "v_add3_u32 %[s], %[s], %[t2], %[t3]\n\t"
+        "v_cndmask_b32 %[t0], 0, %[c4], %[m0]\n\t"
+        "v_cndmask_b32 %[t1], 0, %[c5], %[m1]\n\t"
+        "v_cndmask_b32 %[t2], 0, %[c6], %[m2]\n\t"
+        "v_cndmask_b32 %[t3], 0, %[c7], vcc\n\t"
+        "v_add3_u32 %[s], %[s], %[t0], %[t1]\n\t"
+        "v_add3_u32 %[s], %[s], %[t2], %[t3]"
+        : [s] "+v"(sum), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
+          [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2)
+        : [u0] "v"(u[0]), [u1] "v"(u[1]), [u2] "v"(u[2]), [u3] "v"(u[3]), [u4] "v"(u[4]),
+          [u5] "v"(u[5]), [u6] "v"(u[6]), [u7] "v"(u[7]), [g] "v"(gmax), [c0] "v"(c[0]),
+          [c1] "v"(c[1]), [c2] "v"(c[2]), [c3] "v"(c[3]), [c4] "v"(c[4]), [c5] "v"(c[5]),
+          [c6] "v"(c[6]), [c7] "v"(c[7])
+        : "vcc");
+}
+__device__ __forceinline__ float vmax_chain16(float p, const float *u)
+{
+    asm("v_max3_f32 %0, %0, %1, %2\n\t"
+        "v_max3_f32 %0, %0, %3, %4\n\t"
+        "v_max3_f32 %0, %0, %5, %6\n\t"
+        "v_max3_f32 %0, %0, %7, %8\n\t"
+        "v_max3_f32 %0, %0, %9, %10\n\t"
+        "v_max3_f32 %0, %0, %11, %12\n\t"
+        "v_max3_f32 %0, %0, %13, %14\n\t"
+        "v_max3_f32 %0, %0, %15, %16"
+        : "+v"(p)
+        : "v"(u[0]), "v"(u[1]), "v"(u[2]), "v"(u[3]), "v"(u[4]), "v"(u[5]), "v"(u[6]), "v"(u[7]),
+          "v"(u[8]), "v"(u[9]), "v"(u[10]), "v"(u[11]), "v"(u[12]), "v"(u[13]), "v"(u[14]), "v"(u[15]));
+    return p;
+}
+
 // (a + b) over the two lanes of a candidate, same value in both (integers)
 __device__ __forceinline__ unsigned pair_add_u32(unsigned v)
 {

@@ -342,33 +342,46 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             for (int ct = 0; ct < NT; ++ct) {
                 // lane maximum over this type's registers
                 float pm = -INFINITY;
-                float pend[2];
-                int np = 0;
+                unsigned total = 0u;
+                float gm;
+                if constexpr (N >= 32) {
+                    // whole row tiles belong to the type: one asm block per 16 (maximum) and per
+                    // 8 (compare pass) registers
+                    float u[TPG][16];
 #pragma unroll
-                for (int tt = 0; tt < TPG; ++tt)
+                    for (int tt = 0; tt < TPG; ++tt) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) u[tt][r] = acc[ct][tt][r];
+                        pm = vmax_chain16(pm, u[tt]);
+                    }
+                    gm = pair_max(pm);
+                    static_for<0, TPG, 1>([&](auto ttc) {
+                        constexpr int tt = decltype(ttc)::value;
+                        unsigned ms = 0u;
+                        match8(u[tt], gm, creg, ms);
+                        match8(u[tt] + 8, gm, creg + 8, ms);
+                        if constexpr (tt == 0) total = ms;
+                        else total += ms + (ms >> 16) * (32u * tt);
+                    });
+                } else {
+                    float pend[2];
+                    int np = 0;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        if (N < 32 && acc_row_base(r) / N != ti) continue;
-                        pend[np++] = acc[ct][tt][r];
+                        if (acc_row_base(r) / N != ti) continue;
+                        pend[np++] = acc[ct][0][r];
                         if (np == 2) { pm = vmax3(pm, pend[0], pend[1]); np = 0; }
                     }
-                if (np == 1) pm = vmax2(pm, pend[0]);
-                const float gm = pair_max(pm);
-                // compare pass: per row tile, sum of (action + 2^16) over registers equal to the
-                // maximum; a tile tt stands 32*tt actions up, once per match
-                unsigned total = 0u;
-                static_for<0, TPG, 1>([&](auto ttc) {
-                    constexpr int tt = decltype(ttc)::value;
-                    unsigned ms = 0u;
+                    if (np == 1) pm = vmax2(pm, pend[0]);
+                    gm = pair_max(pm);
+                    // compare pass over the type's registers of the tile
                     static_for<0, 4, 1>([&](auto qc) {
                         constexpr int r = 4 * decltype(qc)::value;
-                        if constexpr (N >= 32 || acc_row_base(r) / N == ti)
-                            match4(acc[ct][tt][r], acc[ct][tt][r + 1], acc[ct][tt][r + 2], acc[ct][tt][r + 3],
-                                   gm, creg[r], creg[r + 1], creg[r + 2], creg[r + 3], ms);
+                        if constexpr (acc_row_base(r) / N == ti)
+                            match4(acc[ct][0][r], acc[ct][0][r + 1], acc[ct][0][r + 2], acc[ct][0][r + 3],
+                                   gm, creg[r], creg[r + 1], creg[r + 2], creg[r + 3], total);
                     });
-                    if constexpr (tt == 0) total = ms;
-                    else total += ms + (ms >> 16) * (32u * tt);
-                });
+                }
                 const unsigned pair = pair_add_u32(total);
                 gmax[ct] = gm;
                 jstar[ct] = (int)(pair & 0xFFFFu);
@@ -478,326 +491,17 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 }
 
 // ------------------------------------------------------------------------------------------
-// Software-pipelined variant for bf16 payoffs, m_pad = 64, n = 128 (the large dense game).
-//
-// On this part the bf16 matrix pipe and the vector ALU run side by side only when one
-// instruction stream feeds both, so this kernel interleaves them by construction: a type's 128
-// actions are cut into two chunks of two row tiles; while the 16 MFMAs of the next chunk are
-// issued one by one, the arg-max epilogue of the previous chunk (whose accumulators sit in the
-// other register set) is executed in 16 pieces between them.  Scheduling fences keep the
-// compiler from undoing the interleave.
-//
-// Per chunk and candidate tile the epilogue is: max3 chain over the lane's 32 values, pair
-// maximum with the partner lane, then a compare pass that adds (action + 2^16) for every
-// register equal to the maximum, so one accumulator yields both the maximising action and
-// the number of maximisers (three vector instructions per value in all, none on the scalar
-// unit); per type the two chunk results are merged (strict greater keeps the lower chunk),
-// and a chunk with other than one maximiser per candidate, or two chunks with equal maxima,
-// send the type through the exact routine.
-//
-// Stages (one type each: 4 row tiles + the type's padded leader rows) go through a ring of
-// three LDS buffers: the copy of stage t+2 is issued at the start of type t, so it has a whole
-// type's time to land; one workgroup barrier per type.
-template <int WAVES>
-__global__ void __launch_bounds__(WAVES * 64, 2)
-sweep_pipe_bf16_kernel(GameView g, SweepArgs a, int /*row_tiles*/)
-{
-    constexpr int MP = 64, N = 128, NT = 2, KS = 4, HALF = 32, TPG = 4;
-    typedef Path<__bf16, MP> P;
-    typedef typename P::frag frag;
-    typedef typename P::xreg xreg;
-    constexpr Geometry G = make_geometry(2, MP, N, TPG, 1, true);
-    typedef const __attribute__((address_space(3))) frag *lds_frag_ptr;
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ float red_v[WAVES];
-    __shared__ long long red_i[WAVES];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int h = lane >> 5, col = lane & 31;
-    const int K = g.K;
-    const unsigned char *records = reinterpret_cast<const unsigned char *>(g.Bpack);
-    const unsigned char *ATpack = reinterpret_cast<const unsigned char *>(g.ATpack);
-    const long long wave_base = ((long long)blockIdx.x * WAVES + wave) * (NT * 32);
-
-    auto prefetch = [&](int st, unsigned ring_off) __attribute__((always_inline)) {
-        const unsigned char *src = records + (size_t)st * G.rec_bytes;
-        unsigned char *dst = smem + ring_off;
-#pragma unroll
-        for (int i = 0; i < (G.rec_bytes / 1024 + WAVES - 1) / WAVES; ++i) {
-            const int chunk = i * WAVES + wave;
-            if (chunk * 1024 < G.rec_bytes)                                 // wave-uniform
-                __builtin_amdgcn_global_load_lds((global_ptr)(src + chunk * 1024 + lane * 16),
-                                                 (lds_ptr)(dst + chunk * 1024), 16, 0, 0);
-        }
-    };
-    unsigned ring0 = 0, ring1 = G.rec_bytes, ring2 = 2 * G.rec_bytes;   // stages t, t+1, t+2
-    prefetch(0, ring0);
-    if (K > 1) prefetch(1, ring1);
-
-    // ---- candidate rows into registers
-    xreg x[NT][P::XREGS];
-    unsigned valid32[NT];
-#pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        const long long c = wave_base + ct * 32 + col;
-        const bool ok = c < a.count;
-        float v[HALF];
-        const float *row = a.X + (ok ? c : 0) * (long long)g.m + h * HALF;
-        if (g.m == MP && ((uintptr_t)a.X & 15) == 0) {
-#pragma unroll
-            for (int e = 0; e < HALF; e += 4) {
-                f32x4 q = ok ? *(const f32x4 *)(row + e) : f32x4{ 0, 0, 0, 0 };
-                v[e] = q[0]; v[e + 1] = q[1]; v[e + 2] = q[2]; v[e + 3] = q[3];
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < HALF; ++e) v[e] = (ok && h * HALF + e < g.m) ? row[e] : 0.0f;
-        }
-        P::pack_x(v, x[ct]);
-        valid32[ct] = (unsigned)__builtin_amdgcn_ballot_w64(ok);
-    }
-
-    float V[NT] = { 0.0f, 0.0f };
-    unsigned tie_count = 0;
-
-    // exact routine (see the plain kernel): recompute the type's tiles from the global records
-    auto exact_type = [&](int ct, int t, float gmax, float &l_out, int &j_out) __attribute__((always_inline)) {
-        float lbest = 0.0f;
-        int jbest = 0, nmatch = 0;
-        const unsigned char *ATt = ATpack + (size_t)t * N * MP * 2;
-#pragma unroll 1
-        for (int tt = 0; tt < TPG; ++tt) {
-            const frag *afrags = reinterpret_cast<const frag *>(records + (size_t)t * G.rec_bytes +
-                                                                (size_t)tt * G.tile_bytes);
-            f32x16 acc1;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) acc1 = P::mfma(afrags[s * 64 + lane], x[ct], s, acc1);
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int r = 4 * q + rr;
-                        const int j = tt * 32 + acc_row_base(r) + 4 * hh;
-                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc1[r] == gmax);
-                        const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid32[ct];
-                        if (hit == 0u) continue;                       // wave-uniform
-                        const float l = pair_sum(
-                            P::half_dot(x[ct], ATt + ((size_t)j * MP + h * HALF) * 2));
-                        if ((hit >> col) & 1u) {
-                            if (nmatch == 0 || l > lbest) { lbest = l; jbest = j; }
-                            ++nmatch;
-                        }
-                    }
-        }
-        l_out = lbest; j_out = jbest;
-        tie_count += __builtin_popcount((unsigned)__builtin_amdgcn_ballot_w64(nmatch >= 2));
-    };
-
-    // two accumulator sets x two candidate tiles x two row tiles of a chunk
-    f32x16 acc[2][NT][2];
-    const f32x16 zero16 = { 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0 };
-
-    // chunk-level results carried between the pieces
-    float pm[NT], gm[NT];
-    unsigned msum[NT][2];           // per row tile: sum over matching registers of (action + 2^16)
-    // type-level state
-    float best[NT];
-    int bidx[NT];
-    bool dirty[NT];
-    // per-register constants of the compare pass: the action a register stands for within its
-    // row tile (lane half included) plus 2^16, so that one accumulator carries both the
-    // matching action and the number of matches
-    unsigned creg[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) creg[r] = (unsigned)(acc_row_base(r) + 4 * h) + 65536u;
-
-    // MFMA number i (0..15) of a chunk into set SET: k-step i/4, row tile (i/2)%2, candidate tile i%2
-    frag fr[8];
-    auto load_frag = [&](lds_frag_ptr tiles, int f) __attribute__((always_inline)) {
-        // fragment f: k-step f/2 of row tile f%2
-        fr[f] = tiles[((f % 2) * KS + f / 2) * 64 + lane];
-    };
-    // one piece of the epilogue of set SET (compile-time piece number)
-    auto epi_piece = [&](auto setc, auto piecec) __attribute__((always_inline)) {
-        constexpr int SET = decltype(setc)::value, PIECE = decltype(piecec)::value;
-        if constexpr (PIECE < 4) {
-            // max3 chain: pieces 0,1 -> candidate tile 0; 2,3 -> candidate tile 1 (16 values each)
-            constexpr int ct = PIECE / 2, tl = PIECE % 2;
-            float p = tl == 0 ? -INFINITY : pm[ct];
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) p = vmax3(p, acc[SET][ct][tl][r], acc[SET][ct][tl][r + 1]);
-            pm[ct] = p;
-            if constexpr (tl == 1) { gm[ct] = pair_max(p); msum[ct][0] = 0u; msum[ct][1] = 0u; }
-        } else {
-            // compare pass over the 32 values of a candidate tile, six pieces, four registers
-            // per step
-            constexpr int ct = (PIECE - 4) / 6, q = (PIECE - 4) % 6;
-            constexpr int first_quad[7] = { 0, 2, 4, 5, 6, 7, 8 };          // 2,2,1,1,1,1 quads
-            static_for<first_quad[q], first_quad[q + 1], 1>([&](auto kc) {
-                constexpr int e = 4 * decltype(kc)::value;
-                constexpr int tl = e / 16, r = e % 16;
-                match4(acc[SET][ct][tl][r], acc[SET][ct][tl][r + 1], acc[SET][ct][tl][r + 2],
-                       acc[SET][ct][tl][r + 3], gm[ct], creg[r], creg[r + 1], creg[r + 2], creg[r + 3],
-                       msum[ct][tl]);
-            });
-        }
-    };
-    // after a candidate tile's compare pass: fold the chunk's result into the type's state
-    auto chunk_tail = [&](auto chunkc, auto ctc) __attribute__((always_inline)) {
-        constexpr int CH = decltype(chunkc)::value, ct = decltype(ctc)::value;
-        // lane total: row tile 1 stands 32 actions above row tile 0, once per match
-        const unsigned lane_sum = msum[ct][0] + msum[ct][1] + ((msum[ct][1] >> 16) << 5);
-        const unsigned pair = pair_add_u32(lane_sum);            // both lanes of the candidate
-        const int jc = (int)(pair & 0xFFFFu) + 64 * CH;          // valid when exactly one match
-        const unsigned multi = (unsigned)__builtin_amdgcn_ballot_w64((pair >> 16) != 1u);
-        const bool chunk_dirty = (multi & valid32[ct]) != 0u || valid32[ct] != 0xFFFFFFFFu;
-        if constexpr (CH == 0) {
-            best[ct] = gm[ct]; bidx[ct] = jc; dirty[ct] = chunk_dirty;
-        } else {
-            const bool cross = (unsigned)__builtin_amdgcn_ballot_w64(gm[ct] == best[ct]) != 0u;
-            bidx[ct] = gm[ct] > best[ct] ? jc : bidx[ct];
-            best[ct] = vmax2(best[ct], gm[ct]);
-            dirty[ct] = dirty[ct] || chunk_dirty || cross;
-        }
-    };
-    auto type_end = [&](int t, float pt, const lds_byte *at_rows, auto ctc) __attribute__((always_inline)) {
-        constexpr int ct = decltype(ctc)::value;
-        float l;
-        int js = bidx[ct];
-        if (!dirty[ct]) {
-            l = pair_sum(P::half_dot(x[ct], at_rows + (unsigned)((js * G.ats + h * HALF) * 2)));
-        } else {
-            exact_type(ct, t, best[ct], l, js);
-        }
-        V[ct] = fmaf(pt, l, V[ct]);
-        if (a.br_out) {
-            const long long c = wave_base + ct * 32 + col;
-            if (h == 0 && c < a.count) a.br_out[c * K + t] = js;
-        }
-    };
-    // 16 MFMAs of a chunk (fragments at `tiles`) into set MSET, interleaved with the epilogue
-    // pieces of the other set (EPI: 0 = nothing to overlap, 1 = chunk 0 of type t, 2 = chunk 1
-    // of type t, whose type-level finish for candidate tile 0 also rides along).  The first
-    // three fragments were loaded by the previous step (pre[]); this step loads the first three
-    // of the next one (next_tiles).
-    frag pre[3];
-    auto step = [&](auto msetc, auto epic, lds_frag_ptr tiles, lds_frag_ptr next_tiles, int t, float pt,
-                    const lds_byte *at_rows) __attribute__((always_inline)) {
-        constexpr int MSET = decltype(msetc)::value;
-        constexpr int EPI = decltype(epic)::value;
-        fr[0] = pre[0]; fr[1] = pre[1]; fr[2] = pre[2];
-        static_for<0, 16, 1>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            constexpr int s = i / 4, tl = (i / 2) % 2, ct = i % 2, f = i / 2;
-            if constexpr (i % 2 == 0 && f + 3 < 8) load_frag(tiles, f + 3);
-            if constexpr (i >= 10 && i % 2 == 0 && (i - 10) / 2 < 3)
-                pre[(i - 10) / 2] = next_tiles[(((i - 10) / 2 % 2) * KS + (i - 10) / 2 / 2) * 64 + lane];
-            acc[MSET][ct][tl] = P::mfma(fr[f], x[ct], s, s == 0 ? zero16 : acc[MSET][ct][tl]);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (EPI != 0) {
-                epi_piece(std::integral_constant<int, 1 - MSET>{}, ic);
-                if constexpr (i == 10) chunk_tail(std::integral_constant<int, EPI - 1>{}, std::integral_constant<int, 0>{});
-                if constexpr (i == 12 && EPI == 2) type_end(t, pt, at_rows, std::integral_constant<int, 0>{});
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
-        if constexpr (EPI != 0) {
-            chunk_tail(std::integral_constant<int, EPI - 1>{}, std::integral_constant<int, 1>{});
-            if constexpr (EPI == 2) type_end(t, pt, at_rows, std::integral_constant<int, 1>{});
-        }
-    };
-
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();                                  // stages 0 and 1 are in LDS
-
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    // chunk 0 of type 0: nothing to overlap with yet
-    {
-        lds_frag_ptr t0 = (lds_frag_ptr)((const lds_byte *)smem + ring0);
-        pre[0] = t0[(0 * KS + 0) * 64 + lane];
-        pre[1] = t0[(1 * KS + 0) * 64 + lane];
-        pre[2] = t0[(0 * KS + 1) * 64 + lane];
-        step(I0{}, I0{}, t0, (lds_frag_ptr)((const lds_byte *)smem + ring0 + 2 * G.tile_bytes), 0, 0.0f, nullptr);
-    }
-
-#pragma unroll 1
-    for (int t = 0; t < K; ++t) {
-        const float pt = g.prior[t];
-        if (t > 0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // own part of stage t+1 has landed
-            __syncthreads();                                    // everyone's has; stage t-1 is dead
-        }
-        if (t + 2 < K) prefetch(t + 2, ring2);
-        const lds_byte *cur = (const lds_byte *)smem + ring0;
-        const lds_byte *nxt = (const lds_byte *)smem + ring1;
-        // chunk 1 of type t  ||  epilogue of chunk 0 of type t
-        step(I1{}, I1{}, (lds_frag_ptr)(cur + 2 * G.tile_bytes), (lds_frag_ptr)nxt, t, pt, nullptr);
-        // chunk 0 of type t+1  ||  epilogue of chunk 1 of type t and the type's finish (past
-        // the last type the MFMAs read a stale buffer; their results are never used)
-        step(I0{}, I2{}, (lds_frag_ptr)nxt, (lds_frag_ptr)(nxt + 2 * G.tile_bytes), t, pt,
-             cur + TPG * G.tile_bytes);
-        const unsigned r0 = ring0; ring0 = ring1; ring1 = ring2; ring2 = r0;
-    }
-
-    // ---- outputs
-    if (a.V_out) {
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            const long long c = wave_base + ct * 32 + col;
-            float v = V[ct];
-            if (!(v == v)) v = -INFINITY;
-            if (h == 0 && c < a.count) a.V_out[c] = v;
-        }
-    }
-    if (a.blk_v) {
-        float bv = -INFINITY;
-        long long bi = LLONG_MAX;
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            const long long c = wave_base + ct * 32 + col;
-            float v = V[ct];
-            if (!(v == v)) v = -INFINITY;
-            if (c < a.count && (v > bv || (v == bv && a.index_base + c < bi))) { bv = v; bi = a.index_base + c; }
-        }
-#pragma unroll
-        for (int d = 16; d >= 1; d >>= 1) {
-            const float ov = __shfl_xor(bv, d, 64);
-            const long long oi = __shfl_xor(bi, d, 64);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
-        __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < WAVES; ++w)
-                if (red_v[w] > bv || (red_v[w] == bv && red_i[w] < bi)) { bv = red_v[w]; bi = red_i[w]; }
-            a.blk_v[blockIdx.x] = bv;
-            a.blk_i[blockIdx.x] = bi;
-        }
-    }
-    if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
-}
-
-// ------------------------------------------------------------------------------------------
 // Instantiation table.
 struct Variant {
     int storage, mp, n, nt, waves, stage_tiles;
     bool at_lds;
     void (*kernel)(GameView, SweepArgs, int);
     Geometry geo;
-    int ring;                    // LDS stage buffers (2: double buffer; 3: pipelined kernel)
 };
 
 #define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv, OCCv, ATL)                                   \
     { ST, MPv, Nv, NTv, Wv, STv, ATL, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv, OCCv, ATL>,   \
-      make_geometry((int)sizeof(T), MPv, Nv, STv, Wv, ATL), 2 }
+      make_geometry((int)sizeof(T), MPv, Nv, STv, Wv, ATL) }
 
 const Variant kVariants[] = {
     // fp32 payoffs
@@ -809,7 +513,7 @@ const Variant kVariants[] = {
     // bf16 payoffs
     BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 2, 2, true),
     BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 2, 2, false),
-    { 1, 64, 128, 2, 8, 4, true, sweep_pipe_bf16_kernel<8>, make_geometry(2, 64, 128, 4, 1, true), 3 },
+    BSSE_VARIANT(__bf16, 1, 64, 128, 2, 4, 4, 2, true),
 };
 
 const Variant *find_variant(int m, int n, int storage)
@@ -852,7 +556,7 @@ hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &
     const long long blocks = mfma_num_blocks(g, kind, a.count);
     const int tiles = row_tiles_for(*v, g.K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
-    const size_t lds = (size_t)v->geo.rec_bytes * (v->ring == 3 ? 3 : (nstages > 1 ? 2 : 1));
+    const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)v->kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
