@@ -23,7 +23,8 @@
  * Arithmetic.  Payoffs are held in fp32 (or bf16, on request) and every sum is
  * accumulated in fp32; "maximiser" and "equal" mean exact equality of the fp32
  * numbers the kernel itself computed.  The summation order inside a dot product is
- * an implementation detail (MFMA paths do not sum in index order).
+ * an implementation detail (MFMA paths do not sum in index order; the split path
+ * forms each product from bf16 parts, see bsse_options.path).
  *
  * Conventions.
  *   - "host" pointers are ordinary process memory; "device" pointers are HIP device
@@ -65,14 +66,22 @@ typedef enum {
 } bsse_status;
 
 enum { BSSE_STORAGE_F32 = 0, BSSE_STORAGE_BF16 = 1 };
-enum { BSSE_PATH_AUTO = 0, BSSE_PATH_VALU = 1, BSSE_PATH_MFMA = 2 };
+enum { BSSE_PATH_AUTO = 0, BSSE_PATH_VALU = 1, BSSE_PATH_MFMA = 2, BSSE_PATH_MFMA_SPLIT = 3 };
 
 typedef struct {
     int storage; /* BSSE_STORAGE_*: how payoffs (and, for BF16, candidates) enter the
                     contraction.  BF16 rounds payoffs and each candidate component to
                     bfloat16 (nearest, ties to even) and accumulates in fp32. */
-    int path;    /* BSSE_PATH_*: AUTO picks MFMA when the shape supports it, else VALU.
-                    MFMA on an unsupported shape is BSSE_EINVAL. */
+    int path;    /* BSSE_PATH_*.  MFMA = matrix cores in the storage type (fp32 MFMA for F32,
+                    bf16 MFMA for BF16).  MFMA_SPLIT (F32 storage only) = bf16 matrix cores on
+                    fp32 operands: every payoff and candidate component is split into bf16
+                    parts hi + mid + lo (exactly, up to the last part's rounding) and the
+                    products hi*hi, hi*mid, mid*hi, hi*lo, mid*mid, lo*hi are accumulated in
+                    fp32 (three products when every payoff is itself a bf16 number); the
+                    omitted products are below 2^-24 of the terms, so the result is within
+                    fp32 rounding of the fp32 dot product.  AUTO picks, in this order, the
+                    small-game kernel, MFMA_SPLIT, MFMA, VALU, by what the shape supports.
+                    A forced path on an unsupported shape is BSSE_EINVAL. */
     int device;  /* HIP device ordinal; -1 = the calling thread's current device */
 } bsse_options;
 
@@ -155,7 +164,8 @@ bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_resp
 bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int64_t count,
                       float *values_dev_out, int32_t *br_dev_out);
 
-/* Which kernel family the handle uses: "valu", "mfma_f32", "mfma_bf16", ... (static string). */
+/* Which kernel family the handle uses: "valu", "mfma_f32", "mfma_bf16", "mfma_split3",
+ * "mfma_split6", ... (static string). */
 const char *bsse_path_name(const bsse_game *g);
 
 /* Kernel timing for roofline reports.  When enabled, every launch of the fused sweep

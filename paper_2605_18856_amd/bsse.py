@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbsse.so")
 
 BSSE_OK, BSSE_EINVAL, BSSE_ENOTFINITE, BSSE_EOVERFLOW, BSSE_ENOMEM, BSSE_EDEVICE, BSSE_ESTATE = range(7)
 BSSE_STORAGE_F32, BSSE_STORAGE_BF16 = 0, 1
-BSSE_PATH_AUTO, BSSE_PATH_VALU, BSSE_PATH_MFMA = 0, 1, 2
+BSSE_PATH_AUTO, BSSE_PATH_VALU, BSSE_PATH_MFMA, BSSE_PATH_MFMA_SPLIT = 0, 1, 2, 3
 
 EXPORTS = [
     "bsse_create", "bsse_create_ex", "bsse_destroy", "bsse_set_stream", "bsse_lattice",

@@ -177,12 +177,13 @@ bsse_status ensure_gen(bsse_game *g, unsigned long long rows)
 hipError_t launch_sweep(bsse_game *g, const SweepArgs &a, bool eval)
 {
     if (g->path == PATH_VALU) return launch_sweep_valu(g->view, a, eval, g->stream);
-    return launch_sweep_mfma(g->view, g->path, a, eval, g->stream);
+    (void)eval;
+    return launch_sweep_mfma(g->view, a, g->stream);
 }
 
 long long sweep_blocks(const bsse_game *g, long long count)
 {
-    return g->path == PATH_VALU ? valu_num_blocks(count) : mfma_num_blocks(g->view, g->path, count);
+    return g->path == PATH_VALU ? valu_num_blocks(count) : mfma_num_blocks(g->view.variant, count);
 }
 
 bsse_status take_event(bsse_game *g, hipEvent_t *e)
@@ -230,7 +231,8 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
     if (elems > (1ull << 28)) return fail(BSSE_EINVAL, "K*m*n = %llu exceeds 2^28", elems);
     if (opt->storage != BSSE_STORAGE_F32 && opt->storage != BSSE_STORAGE_BF16)
         return fail(BSSE_EINVAL, "unknown storage option %d", opt->storage);
-    if (opt->path != BSSE_PATH_AUTO && opt->path != BSSE_PATH_VALU && opt->path != BSSE_PATH_MFMA)
+    if (opt->path != BSSE_PATH_AUTO && opt->path != BSSE_PATH_VALU && opt->path != BSSE_PATH_MFMA &&
+        opt->path != BSSE_PATH_MFMA_SPLIT)
         return fail(BSSE_EINVAL, "unknown path option %d", opt->path);
     if (opt->device < -1) return fail(BSSE_EINVAL, "bad device ordinal %d", opt->device);
     for (unsigned long long e = 0; e < elems; ++e)
@@ -243,9 +245,38 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         psum += (double)prior[t];
     }
     if (std::fabs(psum - 1.0) > 1e-6) return fail(BSSE_EINVAL, "prior sums to %.9g, not 1", psum);
-    const bool can_mfma = mfma_supported(m, n, K, opt->storage);
-    if (opt->path == BSSE_PATH_MFMA && !can_mfma)
-        return fail(BSSE_EINVAL, "shape m=%d n=%d K=%d has no MFMA path", m, n, K);
+    // which kernel family: the small-game kernel, the split path, plain MFMA, else VALU
+    const bool bf = opt->storage == BSSE_STORAGE_BF16;
+    bool exact = true;                       // every payoff is a bf16 number
+    for (unsigned long long e = 0; e < elems && exact; ++e)
+        exact = host_round_bf16(A[e]) == A[e] && host_round_bf16(B[e]) == B[e];
+    int variant = -1;
+    PathKind path = PATH_VALU;
+    if (opt->path == BSSE_PATH_MFMA_SPLIT) {
+        if (bf) return fail(BSSE_EINVAL, "the split path takes fp32 storage");
+        variant = mfma_select(m, n, K, 2, exact);
+        if (variant < 0) return fail(BSSE_EINVAL, "shape m=%d n=%d K=%d has no split MFMA path", m, n, K);
+        path = PATH_MFMA_SPLIT;
+    } else if (opt->path == BSSE_PATH_MFMA) {
+        variant = mfma_select(m, n, K, bf ? 1 : 0, exact);
+        if (variant < 0) return fail(BSSE_EINVAL, "shape m=%d n=%d K=%d has no MFMA path", m, n, K);
+        path = bf ? PATH_MFMA_BF16 : PATH_MFMA_F32;
+    } else if (opt->path == BSSE_PATH_AUTO) {
+        if (bf) {
+            variant = mfma_select(m, n, K, 1, exact);
+            if (variant >= 0) path = PATH_MFMA_BF16;
+        } else {
+            if (small_supported(m, n, K, 0)) {
+                variant = mfma_select(m, n, K, 0, exact);
+                path = PATH_MFMA_F32;
+            } else if ((variant = mfma_select(m, n, K, 2, exact)) >= 0) {
+                path = PATH_MFMA_SPLIT;
+            } else if ((variant = mfma_select(m, n, K, 0, exact)) >= 0) {
+                path = PATH_MFMA_F32;
+            }
+        }
+    }
+    const bool use_mfma = path != PATH_VALU;
 
     // ---- device
     int ndev = 0;
@@ -263,16 +294,14 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
     bsse_game *g = new (std::nothrow) bsse_game;
     if (!g) return fail(BSSE_ENOMEM, "host allocation failed");
     g->m = m; g->n = n; g->K = K; g->storage = opt->storage; g->device = dev;
-    const bool use_mfma = can_mfma && opt->path != BSSE_PATH_VALU;
-    g->path = !use_mfma ? PATH_VALU
-              : (opt->storage == BSSE_STORAGE_BF16 ? PATH_MFMA_BF16 : PATH_MFMA_F32);
+    g->path = path;
+    g->view.variant = variant;
 
     DeviceGuard dg(dev);
     if (!dg.ok) { free_game(g); return fail(BSSE_EDEVICE, "hipSetDevice(%d) failed", dev); }
 
     // ---- pack on the host: optional bf16 rounding, B as given, A transposed per type
     std::vector<float> hB(elems), hAT(elems), hA;
-    const bool bf = opt->storage == BSSE_STORAGE_BF16;
     for (unsigned long long e = 0; e < elems; ++e) hB[e] = bf ? host_round_bf16(B[e]) : B[e];
     for (int t = 0; t < K; ++t)
         for (int i = 0; i < m; ++i)
@@ -300,7 +329,7 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if (use_mfma) {
             void *pb = nullptr, *pa = nullptr;
             size_t bb = 0, ab = 0;
-            mfma_pack(m, n, K, opt->storage, A, B, &pb, &bb, &pa, &ab, &g->view.m_pad, &g->view.n_pad);
+            mfma_pack(variant, m, n, K, A, B, &pb, &bb, &pa, &ab, &g->view.m_pad, &g->view.n_pad);
             if (!pb || !pa) { free(pb); free(pa); st = fail(BSSE_ENOMEM, "host allocation failed"); break; }
             st = up(&g->dBpack, pb, bb);
             if (st == BSSE_OK) st = up(&g->dATpack, pa, ab);
@@ -349,8 +378,9 @@ extern "C" const char *bsse_path_name(const bsse_game *g)
     if (!g) return "";
     switch (g->path) {
     case PATH_VALU: return g->storage == BSSE_STORAGE_BF16 ? "valu_bf16" : "valu";
-    case PATH_MFMA_F32: return "mfma_f32";
-    case PATH_MFMA_BF16: return "mfma_bf16";
+    case PATH_MFMA_F32:
+    case PATH_MFMA_BF16:
+    case PATH_MFMA_SPLIT: return mfma_variant_name(g->view.variant);
     }
     return "";
 }

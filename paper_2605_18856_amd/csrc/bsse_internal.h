@@ -18,6 +18,7 @@ struct GameView {
     const void *ATpack;   // leader payoffs [K][n][m_pad] in the contraction's k order
     int m_pad;            // m rounded up to the MFMA k granularity
     int n_pad;            // n rounded up to the row-tile granularity (see sweep_mfma.hip)
+    int variant;          // matrix-core kernel variant chosen at create (see mfma_select)
 };
 
 // One sweep launch.  Either (V_out, br_out) [evaluation mode: per-candidate outputs] or
@@ -41,21 +42,24 @@ struct RunningBest {
     unsigned long long ties; // tie evaluations of all merged chunks
 };
 
-enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3 };
+enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3, PATH_MFMA_SPLIT = 4 };
 
 // --- launchers (each validates nothing: the API layer has checked shapes) ----------------
 // Number of workgroup records the sweep-mode launch of `count` candidates writes.
 long long valu_num_blocks(long long count);
 hipError_t launch_sweep_valu(const GameView &g, const SweepArgs &a, bool eval, hipStream_t s);
 
-bool mfma_supported(int m, int n, int K, int storage);
-long long mfma_num_blocks(const GameView &g, PathKind kind, long long count);
-hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &a, bool eval,
-                             hipStream_t s);
-// Host-side packing of payoffs for the MFMA paths; returns malloc'ed buffers (caller frees).
-void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
-               void **Bpack, size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad,
-               int *n_pad);
+// Matrix-core variants.  mode: 0 = fp32 MFMA on fp32 payoffs, 1 = bf16 MFMA on bf16-rounded
+// operands, 2 = bf16 MFMA on fp32 operands split into bf16 parts.  `exact` = every payoff is
+// exactly representable in bf16 (lets mode 2 use three terms instead of six).  Returns a
+// variant id >= 0, or -1 when the shape has no such kernel.
+int mfma_select(int m, int n, int K, int mode, bool exact);
+const char *mfma_variant_name(int variant);
+long long mfma_num_blocks(int variant, long long count);
+hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s);
+// Host-side packing of payoffs for a variant; returns malloc'ed buffers (caller frees).
+void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B, void **Bpack,
+               size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad);
 
 // Small-game matrix-core kernel (n = 8, m = 8, K in {4, 8, 12, 16}, fp32); part of the MFMA path.
 bool small_supported(int m, int n, int K, int storage);

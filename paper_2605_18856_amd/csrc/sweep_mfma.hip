@@ -186,10 +186,14 @@ typedef void __attribute__((address_space(3))) *lds_ptr;
 //
 // Stages are double-buffered: the copy of stage s+1 is issued (asynchronously, straight into
 // LDS) before the work on stage s and awaited after it, one workgroup barrier per stage.
-template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS>
+template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS, int TERMS>
 __global__ void __launch_bounds__(WAVES * 64, OCC)
 sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 {
+    static_assert(TERMS == 1 || TERMS == 3 || TERMS == 6, "1 = operands as stored; 3, 6 = split fp32");
+    static_assert(TERMS == 1 || std::is_same<T, __bf16>::value, "split terms run on the bf16 path");
+    static_assert(MP % TERMS == 0, "MP is TERMS blocks of the padded m");
+    constexpr int MP_BASE = MP / TERMS, HALF_BASE = MP_BASE / 2;
     typedef Path<T, MP> P;
     typedef typename P::frag frag;
     typedef typename P::xreg xreg;
@@ -231,26 +235,49 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     };
     prefetch(0);
 
-    // ---- candidate rows into registers: lane (col, h) keeps x[c][h*HALF .. h*HALF+HALF)
+    // ---- candidate rows into registers: lane (col, h) keeps its half of the leader actions,
+    // x[c][h*HALF_BASE .. (h+1)*HALF_BASE); on the split path each component becomes TERMS
+    // bf16 parts, laid out as TERMS blocks of HALF_BASE to match the packed payoffs
     xreg x[NT][P::XREGS];
     unsigned valid32[NT];                     // bit c set iff candidate c of the tile exists
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
         const long long c = wave_base + ct * 32 + col;
         const bool ok = c < a.count;
-        float v[HALF];
-        const float *row = a.X + (ok ? c : 0) * (long long)m + h * HALF;
-        if (m == MP && HALF % 4 == 0 && ((uintptr_t)a.X & 15) == 0) {
+        float vb[HALF_BASE];
+        const float *row = a.X + (ok ? c : 0) * (long long)m + h * HALF_BASE;
+        if (m == MP_BASE && HALF_BASE % 4 == 0 && ((uintptr_t)a.X & 15) == 0) {
 #pragma unroll
-            for (int e = 0; e < HALF; e += 4) {
+            for (int e = 0; e < HALF_BASE; e += 4) {
                 f32x4 q = ok ? *(const f32x4 *)(row + e) : f32x4{ 0, 0, 0, 0 };
-                v[e] = q[0]; v[e + 1] = q[1]; v[e + 2] = q[2]; v[e + 3] = q[3];
+                vb[e] = q[0]; vb[e + 1] = q[1]; vb[e + 2] = q[2]; vb[e + 3] = q[3];
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < HALF; ++e) v[e] = (ok && h * HALF + e < m) ? row[e] : 0.0f;
+            for (int e = 0; e < HALF_BASE; ++e) vb[e] = (ok && h * HALF_BASE + e < m) ? row[e] : 0.0f;
         }
-        P::pack_x(v, x[ct]);
+        if constexpr (TERMS == 1) {
+            P::pack_x(vb, x[ct]);
+        } else {
+            // x = p0 + p1 + p2 with bf16 parts (the subtractions are exact in fp32); blocks pair
+            // with payoff parts as (p0,B0) (p0,B1) (p1,B0) (p0,B2) (p1,B1) (p2,B0), or
+            // (p0,B0) (p1,B0) (p2,B0) when the payoffs are bf16 numbers themselves
+            constexpr int xsel6[6] = { 0, 0, 1, 0, 1, 2 };
+            float v[HALF];
+#pragma unroll
+            for (int e = 0; e < HALF_BASE; ++e) {
+                float part[3];
+                part[0] = __uint_as_float(bf16_bits_rne(vb[e]) << 16);
+                const float r1 = vb[e] - part[0];
+                part[1] = __uint_as_float(bf16_bits_rne(r1) << 16);
+                const float r2 = r1 - part[1];
+                part[2] = __uint_as_float(bf16_bits_rne(r2) << 16);
+#pragma unroll
+                for (int term = 0; term < TERMS; ++term)
+                    v[term * HALF_BASE + e] = part[TERMS == 3 ? term : xsel6[term]];
+            }
+            P::pack_x(v, x[ct]);
+        }
         valid32[ct] = (unsigned)__builtin_amdgcn_ballot_w64(ok);
     }
 
@@ -493,36 +520,40 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 // ------------------------------------------------------------------------------------------
 // Instantiation table.
 struct Variant {
-    int storage, mp, n, nt, waves, stage_tiles;
+    int mode;                    // 0 fp32 MFMA, 1 bf16 MFMA on rounded operands, 2 bf16 MFMA on split fp32
+    int terms;                   // 1, or the number of part products of the split (3 or 6)
+    int mp_base, n, nt, waves, stage_tiles;
     bool at_lds;
     void (*kernel)(GameView, SweepArgs, int);
     Geometry geo;
+    const char *name;
 };
 
-#define BSSE_VARIANT(T, ST, MPv, Nv, NTv, Wv, STv, OCCv, ATL)                                   \
-    { ST, MPv, Nv, NTv, Wv, STv, ATL, sweep_mfma_kernel<T, MPv, Nv, NTv, Wv, STv, OCCv, ATL>,   \
-      make_geometry((int)sizeof(T), MPv, Nv, STv, Wv, ATL) }
+#define BSSE_VARIANT(T, MODE, TERMSv, MPB, Nv, NTv, Wv, STv, OCCv, ATL, NAME)                        \
+    { MODE, TERMSv, MPB, Nv, NTv, Wv, STv, ATL,                                                      \
+      sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv>,                       \
+      make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME }
 
 const Variant kVariants[] = {
-    // fp32 payoffs
-    BSSE_VARIANT(float, 0, 8, 8, 4, 4, 1, 2, true),
-    BSSE_VARIANT(float, 0, 16, 16, 4, 4, 2, 2, true),
-    BSSE_VARIANT(float, 0, 32, 32, 4, 4, 4, 2, true),
-    BSSE_VARIANT(float, 0, 32, 64, 2, 4, 4, 2, true),
-    BSSE_VARIANT(float, 0, 128, 256, 1, 4, 2, 2, false),
-    // bf16 payoffs
-    BSSE_VARIANT(__bf16, 1, 16, 32, 4, 4, 2, 2, true),
-    BSSE_VARIANT(__bf16, 1, 32, 16, 4, 4, 2, 2, false),
-    BSSE_VARIANT(__bf16, 1, 64, 128, 2, 4, 4, 2, true),
+    // fp32 MFMA
+    BSSE_VARIANT(float, 0, 1, 8, 8, 4, 4, 1, 2, true, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 16, 16, 4, 4, 2, 2, true, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 32, 32, 4, 4, 4, 2, true, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 32, 64, 2, 4, 4, 2, true, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 128, 256, 1, 4, 2, 2, false, "mfma_f32"),
+    // bf16 MFMA, operands rounded to bf16
+    BSSE_VARIANT(__bf16, 1, 1, 16, 32, 4, 4, 2, 2, true, "mfma_bf16"),
+    BSSE_VARIANT(__bf16, 1, 1, 32, 16, 4, 4, 2, 2, false, "mfma_bf16"),
+    BSSE_VARIANT(__bf16, 1, 1, 64, 128, 2, 4, 4, 2, true, "mfma_bf16"),
+    // bf16 MFMA on fp32 operands split into bf16 parts
+    BSSE_VARIANT(__bf16, 2, 6, 16, 16, 2, 4, 2, 2, true, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 8, 1, 3, true, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 3, 32, 32, 4, 4, 4, 2, true, "mfma_split3"),
+    BSSE_VARIANT(__bf16, 2, 6, 32, 64, 2, 4, 2, 2, true, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 1, 2, false, "mfma_split3"),
 };
-
-const Variant *find_variant(int m, int n, int storage)
-{
-    const Variant *bestv = nullptr;
-    for (const Variant &v : kVariants)
-        if (v.storage == storage && v.n == n && v.mp >= m && (!bestv || v.mp < bestv->mp)) bestv = &v;
-    return bestv;
-}
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+constexpr int kSmallVariant = 1000;          // the small-game kernel (sweep_small.hip)
 
 int row_tiles_for(const Variant &v, int K)
 {
@@ -531,29 +562,62 @@ int row_tiles_for(const Variant &v, int K)
     return (K + tpt - 1) / tpt;
 }
 
-}  // namespace
-
-bool mfma_supported(int m, int n, int K, int storage)
+// bf16 parts of a value: hi, mid, lo with v = hi + mid + lo up to the rounding of lo
+void bf16_parts(float v, float part[3])
 {
-    return small_supported(m, n, K, storage) || find_variant(m, n, storage) != nullptr;
+    auto rne = [](float f) {
+        uint32_t b; memcpy(&b, &f, 4);
+        b += 0x7FFFu + ((b >> 16) & 1u);
+        b &= 0xFFFF0000u;
+        memcpy(&f, &b, 4);
+        return f;
+    };
+    part[0] = rne(v);
+    const float r1 = v - part[0];
+    part[1] = rne(r1);
+    const float r2 = r1 - part[1];
+    part[2] = rne(r2);
 }
 
-long long mfma_num_blocks(const GameView &g, PathKind kind, long long count)
+}  // namespace
+
+int mfma_select(int m, int n, int K, int mode, bool exact)
 {
-    if (small_supported(g.m, g.n, g.K, kind == PATH_MFMA_BF16 ? 1 : 0)) return small_num_blocks(count);
-    const Variant *v = find_variant(g.m, g.n, kind == PATH_MFMA_BF16 ? 1 : 0);
-    const long long per = (long long)v->nt * 32 * v->waves;
+    if (mode == 0 && small_supported(m, n, K, 0)) return kSmallVariant;
+    int best = -1;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.mode != mode || v.n != n || v.mp_base < m) continue;
+        if (v.terms == 3 && !exact) continue;
+        // smallest padded m wins; among equals, fewer terms
+        if (best < 0 || v.mp_base < kVariants[best].mp_base ||
+            (v.mp_base == kVariants[best].mp_base && v.terms < kVariants[best].terms))
+            best = i;
+    }
+    return best;
+}
+
+const char *mfma_variant_name(int variant)
+{
+    if (variant == kSmallVariant) return "mfma_f32";
+    return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : "";
+}
+
+long long mfma_num_blocks(int variant, long long count)
+{
+    if (variant == kSmallVariant) return small_num_blocks(count);
+    const Variant &v = kVariants[variant];
+    const long long per = (long long)v.nt * 32 * v.waves;
     return (count + per - 1) / per;
 }
 
-hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &a, bool eval,
-                             hipStream_t s)
+hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s)
 {
     if (a.count <= 0) return hipSuccess;
-    if (small_supported(g.m, g.n, g.K, kind == PATH_MFMA_BF16 ? 1 : 0)) return launch_sweep_small(g, a, s);
-    const Variant *v = find_variant(g.m, g.n, kind == PATH_MFMA_BF16 ? 1 : 0);
-    if (!v) return hipErrorNotSupported;
-    const long long blocks = mfma_num_blocks(g, kind, a.count);
+    if (g.variant == kSmallVariant) return launch_sweep_small(g, a, s);
+    if (g.variant < 0 || g.variant >= kNumVariants) return hipErrorNotSupported;
+    const Variant *v = &kVariants[g.variant];
+    const long long blocks = mfma_num_blocks(g.variant, a.count);
     const int tiles = row_tiles_for(*v, g.K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
@@ -567,39 +631,45 @@ hipError_t launch_sweep_mfma(const GameView &g, PathKind kind, const SweepArgs &
 }
 
 // Host packing.
+// The contraction index of a variant runs over MP = terms * mp_base slots.  Lane half h owns
+// slots h*MP/2 .. (h+1)*MP/2; within a half, slot = term * mp_base/2 + (i - h*mp_base/2) for the
+// leader actions i of that half, and the value stored at (term, i) is part q(term) of the payoff:
+// the payoff itself when terms == 1, parts (0,1,0,2,1,0) for six terms, (0,0,0) for three.
 // Bpack = stage records (see Geometry): per stage, STAGE_TILES row tiles, each laid out as
-// [k-step][lane 0..63][fragment], where lane = 32*h + rowInTile supplies leader actions
-// i = h*MP/2 + (elements per lane)*s + e of (type, action) row 32*tile + rowInTile; then, when
-// the variant keeps leader rows in LDS, the rows [type slot][action][MP + pad] of the types the
-// stage covers.  Rows past K*n and actions past m are zero.
-// ATpack = [K][n][MP] leader payoffs in natural action order (zero padded), so that a lane's
-// half of a column is contiguous; used by the global gather and by the exact routine.
-void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B, void **Bpack,
+// [k-step][lane 0..63][fragment], where lane = 32*h + rowInTile supplies the slots
+// h*MP/2 + (elements per lane)*s + e of (type, action) row 32*tile + rowInTile; then, when the
+// variant keeps leader rows in LDS, the rows [type slot][action][MP + pad] of the types the
+// stage covers, in the same slot order.  Rows past K*n and actions past m are zero.
+// ATpack = [K][n][MP] leader payoffs in slot order (zero padded), so that a lane's half of a
+// column is contiguous; used by the global gather and by the exact routine.
+void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B, void **Bpack,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad)
 {
     *Bpack = nullptr; *ATpack = nullptr; *Bbytes = 0; *ATbytes = 0;
-    if (small_supported(m, n, K, storage)) {
+    if (variant == kSmallVariant) {
         *m_pad = 8; *n_pad = n;
         small_pack(m, n, K, A, B, Bpack, Bbytes, ATpack, ATbytes);
         return;
     }
-    const Variant *v = find_variant(m, n, storage);
-    if (!v) return;
+    if (variant < 0 || variant >= kNumVariants) return;
+    const Variant *v = &kVariants[variant];
     const Geometry &G = v->geo;
-    const int MP = v->mp, half = MP / 2;
-    const int epl = storage == 1 ? 8 : 1;                  // k-slots per lane per MFMA
+    const int MP = v->mp_base * v->terms, half = MP / 2, half_base = v->mp_base / 2;
+    const bool bf = v->mode != 0;
+    const int epl = bf ? 8 : 1;                            // k-slots per lane per MFMA
     const int ks = half / epl;
     const int tiles = row_tiles_for(*v, K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
-    const size_t esz = storage == 1 ? 2 : 4;
-    *m_pad = MP; *n_pad = n;
+    const size_t esz = bf ? 2 : 4;
+    static const int bsel6[6] = { 0, 1, 0, 2, 1, 0 };
+    *m_pad = v->mp_base; *n_pad = n;
     *Bbytes = (size_t)nstages * G.rec_bytes;
     *ATbytes = (size_t)K * n * MP * esz;
     unsigned char *pb = (unsigned char *)calloc(*Bbytes, 1);
     unsigned char *pa = (unsigned char *)calloc(*ATbytes, 1);
     if (!pb || !pa) { free(pb); free(pa); return; }
     auto put = [&](unsigned char *base, size_t idx, float val) {
-        if (storage == 1) {
+        if (bf) {
             uint32_t b; memcpy(&b, &val, 4);
             b += 0x7FFFu + ((b >> 16) & 1u);
             const uint16_t hb = (uint16_t)(b >> 16);
@@ -608,6 +678,16 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
             memcpy(base + idx * 4, &val, 4);
         }
     };
+    // value stored at slot `li` (within lane half hh) of payoff matrix M (type t, action j)
+    auto slot_value = [&](const float *M, int t, int j, int hh, int li) -> float {
+        const int term = li / half_base, i = hh * half_base + li % half_base;
+        if (t >= K || i >= m) return 0.0f;
+        const float val = M[((size_t)t * m + i) * n + j];
+        if (v->terms == 1) return val;
+        float part[3];
+        bf16_parts(val, part);
+        return part[v->terms == 3 ? 0 : bsel6[term]];
+    };
     for (int tile = 0; tile < tiles; ++tile) {
         unsigned char *tb = pb + (size_t)(tile / v->stage_tiles) * G.rec_bytes +
                             (size_t)(tile % v->stage_tiles) * G.tile_bytes;
@@ -615,11 +695,8 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
             for (int lane = 0; lane < 64; ++lane) {
                 const int hh = lane / 32, row = tile * 32 + lane % 32;
                 const int t = row / n, j = row % n;
-                for (int e = 0; e < epl; ++e) {
-                    const int i = hh * half + epl * s + e;
-                    const float val = (t < K && i < m) ? B[((size_t)t * m + i) * n + j] : 0.0f;
-                    put(tb, ((size_t)s * 64 + lane) * epl + e, val);
-                }
+                for (int e = 0; e < epl; ++e)
+                    put(tb, ((size_t)s * 64 + lane) * epl + e, slot_value(B, t, j, hh, epl * s + e));
             }
     }
     if (v->at_lds)
@@ -629,14 +706,16 @@ void mfma_pack(int m, int n, int K, int storage, const float *A, const float *B,
                 const int t = st * G.ts + q;
                 if (t >= K) break;
                 for (int j = 0; j < n; ++j)
-                    for (int i = 0; i < m; ++i)
-                        put(ab, ((size_t)q * n + j) * G.ats + i, A[((size_t)t * m + i) * n + j]);
+                    for (int hh = 0; hh < 2; ++hh)
+                        for (int li = 0; li < half; ++li)
+                            put(ab, ((size_t)q * n + j) * G.ats + hh * half + li, slot_value(A, t, j, hh, li));
             }
         }
     for (int t = 0; t < K; ++t)
         for (int j = 0; j < n; ++j)
-            for (int i = 0; i < m; ++i)
-                put(pa, ((size_t)t * n + j) * MP + i, A[((size_t)t * m + i) * n + j]);
+            for (int hh = 0; hh < 2; ++hh)
+                for (int li = 0; li < half; ++li)
+                    put(pa, ((size_t)t * n + j) * MP + hh * half + li, slot_value(A, t, j, hh, li));
     *Bpack = pb; *ATpack = pa;
 }
 

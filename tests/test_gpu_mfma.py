@@ -34,6 +34,56 @@ def test_mfma_path_parity(shape, count):
     _full_check(game, X, bsse.BSSE_PATH_MFMA, "mfma")
 
 
+# (m, n, K, payoff kind): the split path (bf16 matrix cores on fp32 operands cut into bf16 parts);
+# integer payoffs are bf16 numbers and take the three-term variant, the others six terms
+SPLIT_SHAPES = [
+    (16, 16, 3, "normal"), (12, 16, 2, "normal"), (32, 32, 16, "normal"), (20, 32, 5, "normal"),
+    (32, 64, 3, "normal"), (24, 64, 2, "uniform"), (32, 32, 4, "int"), (128, 256, 2, "int"),
+    (100, 256, 1, "int"),
+]
+
+
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "m%dn%dK%d%s" % s)
+@pytest.mark.parametrize("count", [1, 33, 1300, 70001])
+def test_split_path_parity(shape, count):
+    m, n, K, kind = shape
+    game = workloads.small_game(m, n, K, 900 + m + n + K, kind=kind)
+    X = workloads.host_candidates(m, count, 13 + count, "dirichlet")
+    expect = "mfma_split3" if kind == "int" else "mfma_split6"
+    _full_check(game, X, bsse.BSSE_PATH_MFMA_SPLIT, expect)
+
+
+@pytest.mark.parametrize("shape", [(32, 32, 3), (32, 64, 2), (128, 256, 1)], ids=lambda s: "m%dn%dK%d" % s)
+@pytest.mark.parametrize("kind", ["dyadic", "vertex"])
+def test_split_exact_ties(shape, kind):
+    m, n, K = shape
+    game = workloads.small_game(m, n, K, 79, kind="dup")
+    X = workloads.host_candidates(m, 700, 80, kind)
+    # integer payoffs are bf16 numbers: three terms where the shape has such a variant
+    rep, out = _full_check(game, X, bsse.BSSE_PATH_MFMA_SPLIT, "mfma_split6" if n == 64 else "mfma_split3")
+    assert rep.br_mismatch == 0
+    ref = osweep.sweep(game.A, game.B, game.prior, X, diagnostics=True)
+    assert out.n_tie_evals == int((ref.gap == 0).sum()) > 0
+
+
+def test_split_path_rejects_what_it_cannot_do():
+    g8 = workloads.small_game(8, 9, 2, 1)
+    with pytest.raises(bsse.BsseError) as e:
+        bsse.bsse_create(8, 9, 2, g8.A, g8.B, g8.prior, path=bsse.BSSE_PATH_MFMA_SPLIT)
+    assert e.value.status == bsse.BSSE_EINVAL
+    gb = workloads.small_game(32, 32, 2, 1)
+    with pytest.raises(bsse.BsseError) as e:
+        bsse.bsse_create(32, 32, 2, gb.A, gb.B, gb.prior, storage=bsse.BSSE_STORAGE_BF16,
+                         path=bsse.BSSE_PATH_MFMA_SPLIT)
+    assert e.value.status == bsse.BSSE_EINVAL
+    # a real-valued 128x256 game has no six-term variant: forced split fails, AUTO falls back
+    gr = workloads.small_game(128, 256, 1, 2)
+    with pytest.raises(bsse.BsseError):
+        bsse.bsse_create(128, 256, 1, gr.A, gr.B, gr.prior, path=bsse.BSSE_PATH_MFMA_SPLIT)
+    with bsse.bsse_create(128, 256, 1, gr.A, gr.B, gr.prior) as g:
+        assert bsse.bsse_path_name(g) == "mfma_f32"
+
+
 @pytest.mark.parametrize("shape", [(8, 8, 5, "f32"), (8, 8, 4, "f32"), (7, 8, 8, "f32"), (16, 16, 3, "f32"), (32, 32, 3, "f32"),
                                    (32, 64, 2, "f32"), (16, 32, 3, "bf16"), (64, 128, 2, "bf16")],
                          ids=lambda s: "m%dn%dK%d%s" % s)
@@ -110,6 +160,13 @@ def test_config2_full_size():
 
 def test_config3_full_size_sampled():
     _sampled_check(workloads.game(3), 1 << 24, 8192)
+
+
+def test_config3_fp32_mfma_path_sampled():
+    """The plain fp32 MFMA kernel stays reachable and correct when forced."""
+    game = workloads.game(3)
+    X = workloads.host_candidates(game.m, 3000, 5, "dirichlet")
+    _full_check(game, X, bsse.BSSE_PATH_MFMA, "mfma_f32")
 
 
 def test_config4_one_chunk_sampled():
