@@ -92,7 +92,7 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     # the arithmetic unit the path runs on
     flop_peak = PEAK_TFLOPS[path]
     t_hbm = bytes_ / (HBM_PEAK_GBS * 1e9)
-    t_flop = flops / (flop_peak * 1e12)
+    t_flop = flops * EXECUTED_FLOP_FACTOR.get(path, 1.0) / (flop_peak * 1e12)   # what the unit executes
     if t_hbm >= t_flop:
         bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
         achieved = bytes_ / (k_ms * 1e-3) / 1e9
@@ -106,7 +106,12 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
                 "kernel_ms": k_ms, "launches": launches,
                 "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": bytes_}
     if path in EXECUTED_FLOP_FACTOR and bound == "mfma":
+        # the split path does an fp32-accurate contraction with 3 or 6 bf16 products per term:
+        # frac prices the algorithmic flops against the bf16 peak; these fields give the rate the
+        # matrix cores actually run at and the comparison with the fp32 matrix-core peak
         roofline["executed_mfma_tflops"] = achieved * EXECUTED_FLOP_FACTOR[path]
+        roofline["executed_frac"] = achieved * EXECUTED_FLOP_FACTOR[path] / peak
+        roofline["frac_of_fp32_mfma_peak"] = achieved / PEAK_TFLOPS["mfma_f32"]
 
     cpu = None
     if want_cpu_baseline:

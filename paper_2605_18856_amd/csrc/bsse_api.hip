@@ -74,6 +74,7 @@ struct bsse_game {
     RunningBest *run = nullptr;
     float *best_x = nullptr;
     unsigned long long *tie_counter = nullptr;
+    float *win_l = nullptr;  // [K] per-type leader payoffs of the re-evaluated winner
     // pinned host
     HostOut *h_out = nullptr;
     int32_t *h_br = nullptr;
@@ -137,6 +138,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->gen); (void)hipFree(g->lat_table);
     (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
+    (void)hipFree(g->win_l);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -339,6 +341,7 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->win_l, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
         if (e != hipSuccess) { st = fail(BSSE_ENOMEM, "hipHostMalloc: %s", hipGetErrorString(e)); break; }
@@ -553,6 +556,8 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     SweepArgs a{};
     a.X = g->best_x; a.count = 1; a.index_base = 0;
     a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
+    // one row against every type: the general matrix-core kernel spreads the types over the chip
+    if (g->path != PATH_VALU && mfma_slices_types(g->view.variant)) a.l_out = g->win_l;
     HIP_TRY(launch_sweep(g, a, true));
     HIP_TRY(hipStreamSynchronize(g->stream));
     const bool has = g->h_out->run.has != 0;

@@ -32,6 +32,13 @@ struct SweepArgs {
     float *blk_v;            // [nblocks]          (sweep mode)
     long long *blk_i;        // [nblocks] global candidate index, LLONG_MAX if none
     unsigned long long *tie_counter;  // += number of (candidate,type) evaluations with a tie
+    // Type-sliced evaluation (general matrix-core kernel only, evaluation mode): when l_out is set
+    // the launch is split over the types as well, each workgroup writes the leader payoffs
+    // l_t[j*_t] of its slice of types to l_out [count][K], and a second kernel forms V_out from
+    // them in type order (the same sum, term by term, as the unsliced kernel).  For a handful of
+    // rows against many types, where one workgroup walking every type would leave the chip idle.
+    float *l_out;
+    int slice_stages;        // LDS stages per slice (set by the launcher)
 };
 
 // Running best over chunks, in device memory.
@@ -57,6 +64,7 @@ int mfma_select(int m, int n, int K, int mode, bool exact);
 const char *mfma_variant_name(int variant);
 long long mfma_num_blocks(int variant, long long count);
 hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s);
+bool mfma_slices_types(int variant);   // the variant honours SweepArgs::l_out
 // Host-side packing of payoffs for a variant; returns malloc'ed buffers (caller frees).
 void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B, void **Bpack,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad);

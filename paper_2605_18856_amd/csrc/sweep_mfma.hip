@@ -186,7 +186,14 @@ typedef void __attribute__((address_space(3))) *lds_ptr;
 //
 // Stages are double-buffered: the copy of stage s+1 is issued (asynchronously, straight into
 // LDS) before the work on stage s and awaited after it, one workgroup barrier per stage.
-template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS, int TERMS>
+//
+// SLICED: the launch is two-dimensional and workgroup row blockIdx.y walks only its slice of the
+// stages (whole groups), writing the per-type leader payoffs instead of the value; used to
+// re-evaluate a few rows against many types with the whole chip.  The per-candidate instruction
+// sequence does not depend on NT, OCC or SLICED, so every instantiation of a packing gives the
+// same bits for the same row.
+template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS, int TERMS,
+          bool SLICED>
 __global__ void __launch_bounds__(WAVES * 64, OCC)
 sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 {
@@ -217,6 +224,11 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     const unsigned char *ATpack = reinterpret_cast<const unsigned char *>(g.ATpack);
     const long long wave_base = ((long long)blockIdx.x * WAVES + wave) * (NT * 32);
     const int nstages = (row_tiles + STAGE_TILES - 1) / STAGE_TILES;
+    // the stages this workgroup walks: all of them, or slice blockIdx.y of them
+    const int stage_begin = SLICED ? (int)blockIdx.y * a.slice_stages : 0;
+    const int stage_end = SLICED && stage_begin + a.slice_stages < nstages
+                              ? stage_begin + a.slice_stages : nstages;
+    if (SLICED && stage_begin >= stage_end) return;                     // whole workgroup
 
     auto prefetch = [&](int st) __attribute__((always_inline)) {
         const unsigned char *src = records + (size_t)st * G.rec_bytes;
@@ -233,7 +245,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     };
-    prefetch(0);
+    prefetch(stage_begin);
 
     // ---- candidate rows into registers: lane (col, h) keeps its half of the leader actions,
     // x[c][h*HALF_BASE .. (h+1)*HALF_BASE); on the split path each component becomes TERMS
@@ -434,17 +446,21 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                     const long long c = wave_base + ct * 32 + col;
                     if (h == 0 && c < a.count) a.br_out[c * K + t] = js;
                 }
+                if constexpr (SLICED) {
+                    const long long c = wave_base + ct * 32 + col;
+                    if (h == 0 && c < a.count) a.l_out[c * K + t] = l;
+                }
             }
         });
     };
 
-    stage_sync();                              // stage 0 is in LDS
+    stage_sync();                              // the first stage is in LDS
     const int groups = row_tiles / TPG;
     if constexpr (STAGE_TILES >= TPG) {
         constexpr int GPS = STAGE_TILES / TPG;                          // groups per stage
 #pragma unroll 1
-        for (int st = 0; st < nstages; ++st) {
-            if (st + 1 < nstages) prefetch(st + 1);
+        for (int st = stage_begin; st < stage_end; ++st) {
+            if (st + 1 < stage_end) prefetch(st + 1);
             const unsigned char *buf = smem + (st & 1) * G.rec_bytes;
             const frag *tiles = reinterpret_cast<const frag *>(buf);
             const int g0 = st * GPS;
@@ -460,13 +476,14 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         }
     } else {
         constexpr int SPG = TPG / STAGE_TILES;                          // stages per group
-        int st = 0;
+        int st = stage_begin;                                           // a multiple of SPG
+        const int group_end = stage_end / SPG < groups ? stage_end / SPG : groups;
 #pragma unroll 1
-        for (int gr = 0; gr < groups; ++gr) {
+        for (int gr = stage_begin / SPG; gr < group_end; ++gr) {
             zero_acc();
             static_for<0, SPG, 1>([&](auto ssc) {
                 constexpr int ss = decltype(ssc)::value;
-                if (st + 1 < nstages) prefetch(st + 1);
+                if (st + 1 < stage_end) prefetch(st + 1);
                 const frag *tiles = reinterpret_cast<const frag *>(smem + (st & 1) * G.rec_bytes);
                 static_for<0, STAGE_TILES, 1>([&](auto t2c) {
                     constexpr int t2 = decltype(t2c)::value;
@@ -480,7 +497,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     }
 
     // ---- outputs
-    if (a.V_out) {
+    if (!SLICED && a.V_out) {
 #pragma unroll
         for (int ct = 0; ct < NT; ++ct) {
             const long long c = wave_base + ct * 32 + col;
@@ -517,6 +534,20 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
 }
 
+// Second step of the type-sliced evaluation: V[c] = sum_t prior[t] * l[c][t], one lane per row,
+// accumulated in type order with the fused multiply-add of the unsliced kernel, so the value is
+// the same fp32 number.
+__global__ void finish_value_kernel(const float *__restrict__ prior, const float *__restrict__ l,
+                                    int K, long long count, float *__restrict__ V_out)
+{
+    const long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= count) return;
+    float v = 0.0f;
+    for (int t = 0; t < K; ++t) v = fmaf(prior[t], l[c * K + t], v);
+    if (!(v == v)) v = -INFINITY;
+    V_out[c] = v;
+}
+
 // ------------------------------------------------------------------------------------------
 // Instantiation table.
 struct Variant {
@@ -525,13 +556,15 @@ struct Variant {
     int mp_base, n, nt, waves, stage_tiles;
     bool at_lds;
     void (*kernel)(GameView, SweepArgs, int);
+    void (*sliced)(GameView, SweepArgs, int);     // one candidate tile per wavefront, types sliced
     Geometry geo;
     const char *name;
 };
 
 #define BSSE_VARIANT(T, MODE, TERMSv, MPB, Nv, NTv, Wv, STv, OCCv, ATL, NAME)                        \
     { MODE, TERMSv, MPB, Nv, NTv, Wv, STv, ATL,                                                      \
-      sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv>,                       \
+      sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv, false>,                \
+      sweep_mfma_kernel<T, MPB * TERMSv, Nv, 1, Wv, STv, 1, ATL, TERMSv, true>,                      \
       make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME }
 
 const Variant kVariants[] = {
@@ -603,6 +636,8 @@ const char *mfma_variant_name(int variant)
     return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : "";
 }
 
+bool mfma_slices_types(int variant) { return variant >= 0 && variant < kNumVariants; }
+
 long long mfma_num_blocks(int variant, long long count)
 {
     if (variant == kSmallVariant) return small_num_blocks(count);
@@ -617,16 +652,35 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
     if (g.variant == kSmallVariant) return launch_sweep_small(g, a, s);
     if (g.variant < 0 || g.variant >= kNumVariants) return hipErrorNotSupported;
     const Variant *v = &kVariants[g.variant];
-    const long long blocks = mfma_num_blocks(g.variant, a.count);
     const int tiles = row_tiles_for(*v, g.K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
+    auto kernel = a.l_out ? v->sliced : v->kernel;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)v->kernel,
+        hipError_t e = hipFuncSetAttribute((const void *)kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(v->kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
+    if (!a.l_out) {
+        const long long blocks = mfma_num_blocks(g.variant, a.count);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
+        return hipGetLastError();
+    }
+    // type-sliced evaluation: 32 candidates per wavefront, whole groups per slice, about kSlices
+    // slices
+    const long long per = 32LL * v->waves, blocks = (a.count + per - 1) / per;
+    if (a.blk_v || blocks > 65535) return hipErrorInvalidValue;
+    constexpr int kSlices = 256;
+    const int spg = v->geo.tpg > v->stage_tiles ? v->geo.tpg / v->stage_tiles : 1;   // stages per group
+    SweepArgs b = a;
+    b.slice_stages = ((nstages + kSlices - 1) / kSlices + spg - 1) / spg * spg;
+    const int slices = (nstages + b.slice_stages - 1) / b.slice_stages;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks, (unsigned)slices), dim3(v->waves * 64), lds, s, g, b,
+                       tiles);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !a.V_out) return e;
+    hipLaunchKernelGGL(finish_value_kernel, dim3((unsigned)((a.count + 63) / 64)), dim3(64), 0, s,
+                       g.prior, a.l_out, g.K, a.count, a.V_out);
     return hipGetLastError();
 }
 
