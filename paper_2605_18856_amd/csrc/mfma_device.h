@@ -128,6 +128,86 @@ __device__ __forceinline__ void match8(const float *u, float gmax, const unsigne
           [c6] "v"(c[6]), [c7] "v"(c[7])
         : "vcc");
 }
+// Compare pass as a bitmap: sixteen values against the maximum, bits = (bits << 16) | e with
+// bit 15 - r of e set iff u[r] == gmax.  One compare and one add-with-carry (bits + bits + carry)
+// per value; the four compares of a group precede the four adds that read their masks, which
+// also keeps the two wait states a vector read of a vector-written scalar register needs.
+__device__ __forceinline__ void bitmap16(const float *u, float gmax, unsigned &bits)
+{
+    unsigned long long m0, m1, m2;
+#define BSSE_BM4(a, b, c, d)                                                    \
+        "v_cmp_eq_f32 %[m0], %[u" #a "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m1], %[u" #b "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m2], %[u" #c "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 vcc, %[u" #d "], %[g]\n\t"                                \
+        "v_addc_co_u32_e64 %[b], %[m0], %[b], %[b], %[m0]\n\t"                  \
+        "v_addc_co_u32_e64 %[b], %[m1], %[b], %[b], %[m1]\n\t"                  \
+        "v_addc_co_u32_e64 %[b], %[m2], %[b], %[b], %[m2]\n\t"                  \
+        "v_addc_co_u32_e32 %[b], vcc, %[b], %[b], vcc\n\t"
+    asm(BSSE_BM4(0, 1, 2, 3) BSSE_BM4(4, 5, 6, 7) BSSE_BM4(8, 9, 10, 11) BSSE_BM4(12, 13, 14, 15)
+        : [b] "+v"(bits), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2)
+        : [u0] "v"(u[0]), [u1] "v"(u[1]), [u2] "v"(u[2]), [u3] "v"(u[3]), [u4] "v"(u[4]),
+          [u5] "v"(u[5]), [u6] "v"(u[6]), [u7] "v"(u[7]), [u8] "v"(u[8]), [u9] "v"(u[9]),
+          [u10] "v"(u[10]), [u11] "v"(u[11]), [u12] "v"(u[12]), [u13] "v"(u[13]), [u14] "v"(u[14]),
+          [u15] "v"(u[15]), [g] "v"(gmax)
+        : "vcc");
+#undef BSSE_BM4
+}
+// Two independent streams interleaved instruction by instruction: a wavefront that is alone in
+// its epilogue (its neighbour on the SIMD being busy with MFMAs) issues dependent vector
+// instructions at about half rate, independent ones at nearly full rate.
+__device__ __forceinline__ void bitmap16x2(const float *ua, float ga, unsigned &ba, const float *ub,
+                                           float gb, unsigned &bb)
+{
+    unsigned long long m0, m1, m2, m3, m4, m5, m6;
+#define BSSE_BM4X2(a, b, c, d)                                                  \
+        "v_cmp_eq_f32 %[m0], %[ua" #a "], %[ga]\n\t"                            \
+        "v_cmp_eq_f32 %[m1], %[ub" #a "], %[gb]\n\t"                            \
+        "v_cmp_eq_f32 %[m2], %[ua" #b "], %[ga]\n\t"                            \
+        "v_cmp_eq_f32 %[m3], %[ub" #b "], %[gb]\n\t"                            \
+        "v_cmp_eq_f32 %[m4], %[ua" #c "], %[ga]\n\t"                            \
+        "v_cmp_eq_f32 %[m5], %[ub" #c "], %[gb]\n\t"                            \
+        "v_cmp_eq_f32 %[m6], %[ua" #d "], %[ga]\n\t"                            \
+        "v_cmp_eq_f32 vcc, %[ub" #d "], %[gb]\n\t"                              \
+        "v_addc_co_u32_e64 %[ba], %[m0], %[ba], %[ba], %[m0]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m1], %[bb], %[bb], %[m1]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m2], %[ba], %[ba], %[m2]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m3], %[bb], %[bb], %[m3]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m4], %[ba], %[ba], %[m4]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m5], %[bb], %[bb], %[m5]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m6], %[ba], %[ba], %[m6]\n\t"               \
+        "v_addc_co_u32_e32 %[bb], vcc, %[bb], %[bb], vcc\n\t"
+#define BSSE_U4(x, a, b, c, d) [x##a] "v"(x[a]), [x##b] "v"(x[b]), [x##c] "v"(x[c]), [x##d] "v"(x[d])
+    asm(BSSE_BM4X2(0, 1, 2, 3) BSSE_BM4X2(4, 5, 6, 7) BSSE_BM4X2(8, 9, 10, 11) BSSE_BM4X2(12, 13, 14, 15)
+        : [ba] "+v"(ba), [bb] "+v"(bb), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+          [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6)
+        : BSSE_U4(ua, 0, 1, 2, 3), BSSE_U4(ua, 4, 5, 6, 7), BSSE_U4(ua, 8, 9, 10, 11),
+          BSSE_U4(ua, 12, 13, 14, 15), BSSE_U4(ub, 0, 1, 2, 3), BSSE_U4(ub, 4, 5, 6, 7),
+          BSSE_U4(ub, 8, 9, 10, 11), BSSE_U4(ub, 12, 13, 14, 15), [ga] "v"(ga), [gb] "v"(gb)
+        : "vcc");
+#undef BSSE_BM4X2
+}
+__device__ __forceinline__ void vmax_chain16x2(float &pa, const float *ua, float &pb, const float *ub)
+{
+#define BSSE_MX(a, b)                                                           \
+        "v_max3_f32 %[pa], %[pa], %[ua" #a "], %[ua" #b "]\n\t"                  \
+        "v_max3_f32 %[pb], %[pb], %[ub" #a "], %[ub" #b "]\n\t"
+    asm(BSSE_MX(0, 1) BSSE_MX(2, 3) BSSE_MX(4, 5) BSSE_MX(6, 7) BSSE_MX(8, 9) BSSE_MX(10, 11)
+        BSSE_MX(12, 13) BSSE_MX(14, 15)
+        : [pa] "+v"(pa), [pb] "+v"(pb)
+        : BSSE_U4(ua, 0, 1, 2, 3), BSSE_U4(ua, 4, 5, 6, 7), BSSE_U4(ua, 8, 9, 10, 11),
+          BSSE_U4(ua, 12, 13, 14, 15), BSSE_U4(ub, 0, 1, 2, 3), BSSE_U4(ub, 4, 5, 6, 7),
+          BSSE_U4(ub, 8, 9, 10, 11), BSSE_U4(ub, 12, 13, 14, 15));
+#undef BSSE_MX
+#undef BSSE_U4
+}
+// number of leading zero bits; 0xFFFFFFFF for zero
+__device__ __forceinline__ unsigned ffbh(unsigned x)
+{
+    unsigned r;
+    asm("v_ffbh_u32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
 __device__ __forceinline__ float vmax_chain16(float p, const float *u)
 {
     asm("v_max3_f32 %0, %0, %1, %2\n\t"

@@ -384,24 +384,54 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 unsigned total = 0u;
                 float gm;
                 if constexpr (N >= 32) {
-                    // whole row tiles belong to the type: one asm block per 16 (maximum) and per
-                    // 8 (compare pass) registers
+                    // whole row tiles belong to the type: one asm block per 16 registers for the
+                    // maximum and one for the compare pass
                     float u[TPG][16];
 #pragma unroll
-                    for (int tt = 0; tt < TPG; ++tt) {
+                    for (int tt = 0; tt < TPG; ++tt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) u[tt][r] = acc[ct][tt][r];
-                        pm = vmax_chain16(pm, u[tt]);
+                    if constexpr (TPG == 1) {
+                        pm = vmax_chain16(pm, u[0]);
+                        gm = pair_max(pm);
+                        match8(u[0], gm, creg, total);
+                        match8(u[0] + 8, gm, creg + 8, total);
+                    } else {
+                        // tile tt goes with tile tt + TPG/2: two independent instruction streams
+                        constexpr int HT = TPG / 2;
+                        float pb = -INFINITY;
+                        static_for<0, HT, 1>([&](auto ttc) {
+                            constexpr int tt = decltype(ttc)::value;
+                            vmax_chain16x2(pm, u[tt], pb, u[tt + HT]);
+                        });
+                        gm = pair_max(vmax2(pm, pb));
+                        // compare pass as a bitmap: one bit per value, first value highest; 32
+                        // values (two row tiles) per word
+                        constexpr int NW = HT;
+                        unsigned w[NW];
+                        if constexpr (TPG == 2) {
+                            unsigned wa = 0u, wb = 0u;
+                            bitmap16x2(u[0], gm, wa, u[1], gm, wb);
+                            w[0] = (wa << 16) | wb;
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < NW; ++k) w[k] = 0u;
+                            static_for<0, HT, 1>([&](auto ttc) {
+                                constexpr int tt = decltype(ttc)::value;
+                                bitmap16x2(u[tt], gm, w[tt / 2], u[tt + HT], gm, w[(tt + HT) / 2]);
+                            });
+                        }
+                        unsigned cnt = 0u, pos = 0xFFFFFFFFu;  // maximisers of the lane; first one
+#pragma unroll
+                        for (int k = 0; k < NW; ++k) {
+                            cnt += (unsigned)__builtin_popcount(w[k]);
+                            const unsigned f = ffbh(w[k]) | (32u * k);   // stays 0xFFFFFFFF for no bit
+                            pos = f < pos ? f : pos;
+                        }
+                        // position = 16 * tile + register  ->  action 32 * tile + row(register) + 4h
+                        const unsigned act = ((pos & 0xFCu) << 1) | (pos & 3u) | (4u * h);
+                        total = cnt ? (cnt << 16) | act : 0u;
                     }
-                    gm = pair_max(pm);
-                    static_for<0, TPG, 1>([&](auto ttc) {
-                        constexpr int tt = decltype(ttc)::value;
-                        unsigned ms = 0u;
-                        match8(u[tt], gm, creg, ms);
-                        match8(u[tt] + 8, gm, creg + 8, ms);
-                        if constexpr (tt == 0) total = ms;
-                        else total += ms + (ms >> 16) * (32u * tt);
-                    });
                 } else {
                     float pend[2];
                     int np = 0;
