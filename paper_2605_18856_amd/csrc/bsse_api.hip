@@ -531,9 +531,18 @@ extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_de
         g->ev.push_back(e0); g->ev.push_back(e1);
     }
     HIP_TRY(le);
-    HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, candidates_dev, index_base, g->m,
-                                g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
-                                g->stream));
+    if (g->path != PATH_VALU && mfma_is_small(g->view.variant)) {
+        // grid stage, merge and the best responses of a new running best in one launch
+        FinishArgs f{};
+        f.nblocks = nblocks; f.first = g->fresh ? 1 : 0;
+        f.run = g->run; f.run_host = &g->h_out->run; f.best_x = g->best_x;
+        f.win_v = &g->h_out->fin_v; f.win_br = g->h_br;
+        HIP_TRY(launch_finish_small(g->view, a, f, g->stream));
+    } else {
+        HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, candidates_dev, index_base, g->m,
+                                    g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
+                                    g->stream));
+    }
     g->fresh = false;
     g->n_evals += (long long)count * g->K;
     return BSSE_OK;
@@ -553,12 +562,14 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     }
     // best responses of the winner: the same kernel, one row, per-candidate outputs written
     // straight into pinned host memory
-    SweepArgs a{};
-    a.X = g->best_x; a.count = 1; a.index_base = 0;
-    a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
-    // one row against every type: the general matrix-core kernel spreads the types over the chip
-    if (g->path != PATH_VALU && mfma_slices_types(g->view.variant)) a.l_out = g->win_l;
-    HIP_TRY(launch_sweep(g, a, true));
+    if (!(g->path != PATH_VALU && mfma_is_small(g->view.variant))) {   // (that path has done it already)
+        SweepArgs a{};
+        a.X = g->best_x; a.count = 1; a.index_base = 0;
+        a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
+        // one row against every type: the general matrix-core kernel spreads the types over the chip
+        if (g->path != PATH_VALU && mfma_slices_types(g->view.variant)) a.l_out = g->win_l;
+        HIP_TRY(launch_sweep(g, a, true));
+    }
     HIP_TRY(hipStreamSynchronize(g->stream));
     const bool has = g->h_out->run.has != 0;
     if (has && !(g->h_out->fin_v == g->h_out->run.value))

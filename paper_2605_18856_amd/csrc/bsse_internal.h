@@ -49,6 +49,18 @@ struct RunningBest {
     unsigned long long ties; // tie evaluations of all merged chunks
 };
 
+// Grid stage of a sweep launch fused with the re-evaluation of a new running best (small-game
+// path): the records of `nblocks` workgroups are in SweepArgs::blk_v / blk_i.
+struct FinishArgs {
+    long long nblocks;
+    int first;               // != 0: the running best is replaced, not merged
+    RunningBest *run;        // device
+    RunningBest *run_host;   // device-visible pinned host memory
+    float *best_x;           // [m] row of the running best
+    float *win_v;            // value of the re-evaluated row (pinned host)
+    int32_t *win_br;         // [K] its best responses (pinned host)
+};
+
 enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3, PATH_MFMA_SPLIT = 4 };
 
 // --- launchers (each validates nothing: the API layer has checked shapes) ----------------
@@ -65,6 +77,7 @@ const char *mfma_variant_name(int variant);
 long long mfma_num_blocks(int variant, long long count);
 hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s);
 bool mfma_slices_types(int variant);   // the variant honours SweepArgs::l_out
+bool mfma_is_small(int variant);       // the small-game kernel: launch_finish_small applies
 // Host-side packing of payoffs for a variant; returns malloc'ed buffers (caller frees).
 void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B, void **Bpack,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad);
@@ -73,6 +86,7 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
 bool small_supported(int m, int n, int K, int storage);
 long long small_num_blocks(long long count);
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s);
+hipError_t launch_finish_small(const GameView &g, const SweepArgs &a, const FinishArgs &f, hipStream_t s);
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes);
 

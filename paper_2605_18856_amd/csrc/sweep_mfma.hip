@@ -666,6 +666,7 @@ const char *mfma_variant_name(int variant)
     return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : "";
 }
 
+bool mfma_is_small(int variant) { return variant == kSmallVariant; }
 bool mfma_slices_types(int variant) { return variant >= 0 && variant < kNumVariants; }
 
 long long mfma_num_blocks(int variant, long long count)

@@ -29,10 +29,11 @@ constexpr int SM_AT_STRIDE = 12;       // floats per leader row in LDS (8 + pad:
 constexpr int SM_MAX_TILES = 4;
 
 // TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
-// Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).
+// Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).  The body of a
+// workgroup; block / nblocks are its place in the (one-dimensional) grid of the pass.
 template <int TILES, bool EVAL>
-__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
-sweep_small_kernel(GameView g, SweepArgs a)
+__device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a, unsigned block,
+                                           unsigned nblocks)
 {
     __shared__ __attribute__((aligned(16))) float at_lds[TILES * 4 * SM_N * SM_AT_STRIDE];
     __shared__ float red_v[SM_WAVES];
@@ -46,8 +47,8 @@ sweep_small_kernel(GameView g, SweepArgs a)
 
     const unsigned per_iter = SM_NT * 32;
     const unsigned n_tasks = (count + per_iter - 1) / per_iter;
-    const unsigned task0 = blockIdx.x * SM_WAVES + wave;
-    const unsigned task_stride = gridDim.x * SM_WAVES;
+    const unsigned task0 = block * SM_WAVES + wave;
+    const unsigned task_stride = nblocks * SM_WAVES;
 
     // candidate rows of one task: own = x[4h..4h+3] (the MFMA k-slots of this lane half),
     // oth = the other four components (needed for the leader payoff only)
@@ -224,11 +225,72 @@ sweep_small_kernel(GameView g, SweepArgs a)
                 if (red_v[w] > best_v || (red_v[w] == best_v && red_c[w] < best_c)) {
                     best_v = red_v[w]; best_c = red_c[w];
                 }
-            a.blk_v[blockIdx.x] = best_v;
-            a.blk_i[blockIdx.x] = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
+            a.blk_v[block] = best_v;
+            a.blk_i[block] = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
         }
         if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
     }
+}
+
+template <int TILES, bool EVAL>
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
+sweep_small_kernel(GameView g, SweepArgs a)
+{
+    small_body<TILES, EVAL>(g, a, blockIdx.x, gridDim.x);
+}
+
+// Steps 5-6 for the small-game path in one single-workgroup launch: fold the workgroup records
+// of a sweep launch (greatest value, lowest index among equals), merge into the running best
+// with a strict "greater than", and, when the running best changed, keep its row and evaluate
+// it again with per-candidate outputs, which gives its K best responses (same instruction
+// sequence as the sweep, hence the same value bit for bit).
+template <int TILES>
+__global__ void __launch_bounds__(SM_WAVES * 64)
+small_finish_kernel(GameView g, SweepArgs a, FinishArgs f)
+{
+    __shared__ float sv[SM_WAVES];
+    __shared__ long long si[SM_WAVES];
+    __shared__ long long win;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float bv = -INFINITY;
+    long long bi = LLONG_MAX;
+    for (long long b = tid; b < f.nblocks; b += SM_WAVES * 64) {
+        const float v = a.blk_v[b];
+        const long long i = a.blk_i[b];
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float ov = __shfl_xor(bv, d, 64);
+        const long long oi = __shfl_xor(bi, d, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < SM_WAVES; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        long long w_row = -1;
+        RunningBest r = *f.run;
+        if (f.first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
+        if (bi != LLONG_MAX && (!r.has || bv > r.value)) {
+            r.value = bv; r.index = bi; r.has = 1;
+            w_row = bi - a.index_base;
+        }
+        r.ties += *a.tie_counter;
+        *a.tie_counter = 0ull;                   // the next chunk starts from zero
+        *f.run = r;
+        *f.run_host = r;
+        win = w_row;
+    }
+    __syncthreads();
+    const long long row = win;
+    if (row < 0) return;                         // whole workgroup
+    if (tid < SM_M) f.best_x[tid] = a.X[row * SM_M + tid];
+    SweepArgs e{};
+    e.X = a.X + row * SM_M; e.count = 1; e.index_base = 0;
+    e.V_out = f.win_v; e.br_out = f.win_br;
+    small_body<TILES, true>(g, e, 0u, 1u);
 }
 
 typedef void (*small_kernel_t)(GameView, SweepArgs);
@@ -239,6 +301,18 @@ small_kernel_t small_kernel_for(int K, bool eval)
     case 2: return eval ? sweep_small_kernel<2, true> : sweep_small_kernel<2, false>;
     case 3: return eval ? sweep_small_kernel<3, true> : sweep_small_kernel<3, false>;
     case 4: return eval ? sweep_small_kernel<4, true> : sweep_small_kernel<4, false>;
+    }
+    return nullptr;
+}
+
+typedef void (*small_finish_t)(GameView, SweepArgs, FinishArgs);
+small_finish_t small_finish_for(int K)
+{
+    switch (K / 4) {
+    case 1: return small_finish_kernel<1>;
+    case 2: return small_finish_kernel<2>;
+    case 3: return small_finish_kernel<3>;
+    case 4: return small_finish_kernel<4>;
     }
     return nullptr;
 }
@@ -266,6 +340,15 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
     if (!k) return hipErrorNotSupported;
     if (((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
     hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_small(const GameView &g, const SweepArgs &a, const FinishArgs &f, hipStream_t s)
+{
+    if (f.nblocks <= 0) return hipSuccess;
+    small_finish_t k = small_finish_for(g.K);
+    if (!k) return hipErrorNotSupported;
+    hipLaunchKernelGGL(k, dim3(1), dim3(SM_WAVES * 64), 0, s, g, a, f);
     return hipGetLastError();
 }
 
