@@ -119,7 +119,7 @@ bsse_status bsse_set_stream(bsse_game *g, void *hip_stream);
  * bsse_lattice_count: the same count, host only (no device needed).
  *
  * bsse_dirichlet: rows first..first+count-1 of the seeded sequence of points uniform
- * on the simplex (flat Dirichlet): component i of row c is g_i / sum_i g_i with
+ * on the simplex (flat Dirichlet): component i of row c is g_i * fl32(1 / sum_i g_i) with
  * g_i = -ln(u_i), u_i = ((w_i >> 8) + 1) / 2^24, and w the output words of
  * Philox4x32-10 keyed by (seed low word, seed high word) at counter
  * (c low word, c high word, i / 4, 0), word i % 4.  Row c depends on (seed, c) only.

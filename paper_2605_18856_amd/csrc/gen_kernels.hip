@@ -57,12 +57,22 @@ hipError_t launch_lattice(const unsigned long long *table, int m, int N, long lo
 // advances by two Weyl constants between rounds.
 struct U4 { unsigned x, y, z, w; };
 
+__device__ __forceinline__ unsigned long long mul_wide(unsigned a, unsigned b)
+{
+    unsigned long long d;
+    asm("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(d) : "s"(a), "v"(b) : "vcc");
+    return d;
+}
+
 __device__ __forceinline__ U4 philox4x32_10(U4 c, unsigned k0, unsigned k1)
 {
 #pragma unroll
     for (int rnd = 0; rnd < 10; ++rnd) {
-        const unsigned hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
-        const unsigned hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        // one 32x32->64 multiply-add instruction per product (full rate on this part; the
+        // compiler would otherwise issue separate high and low multiplies)
+        const unsigned long long p0 = mul_wide(0xD2511F53u, c.x), p1 = mul_wide(0xCD9E8D57u, c.z);
+        const unsigned hi0 = (unsigned)(p0 >> 32), lo0 = (unsigned)p0;
+        const unsigned hi1 = (unsigned)(p1 >> 32), lo1 = (unsigned)p1;
         U4 d;
         d.x = hi1 ^ c.y ^ k0;
         d.y = lo1;
@@ -79,7 +89,12 @@ __device__ __forceinline__ U4 philox4x32_10(U4 c, unsigned k0, unsigned k1)
 __device__ __forceinline__ float unit_exponential(unsigned w)
 {
     const float u = (float)((w >> 8) + 1u) * 5.9604644775390625e-08f;   // exact: < 2^24+1
-    return -logf(u);
+    // -ln u = -log2(u) * ln 2 with the product carried in two parts; u >= 2^-24 is never
+    // subnormal, so the hardware logarithm needs no range scaling
+    const float r = __builtin_amdgcn_logf(u);
+    const float c = 0x1.62e42ep-1f, cc = 0x1.efa39ep-25f;                // ln 2 = c + cc
+    const float y = r * c;
+    return -(y + fmaf(r, cc, fmaf(r, c, -y)));
 }
 
 // One thread per (row, group of four components): one Philox call, one float4 store, so a
@@ -108,7 +123,8 @@ dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count
         for (int d = 1; d < nb; d <<= 1) sum += __shfl_xor(sum, d, 64);
         float4 v;
         if (sum > 0.0f) {
-            v = make_float4(g0 / sum, g1 / sum, g2 / sum, g3 / sum);
+            const float inv = 1.0f / sum;                                // correctly rounded
+            v = make_float4(g0 * inv, g1 * inv, g2 * inv, g3 * inv);
         } else {
             const float e = 1.0f / (float)m;
             v = make_float4(e, e, e, e);
@@ -135,13 +151,14 @@ dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count,
             for (int e = 0; e < 4; ++e)
                 if (4 * b + e < m) sum += unit_exponential(ww[e]);
         }
+        const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;                // correctly rounded
         for (int b = 0; b < nb; ++b) {
             const U4 w = philox4x32_10(U4{ c0, c1, (unsigned)b, 0u }, k0, k1);
             const unsigned ww[4] = { w.x, w.y, w.z, w.w };
             for (int e = 0; e < 4; ++e)
                 if (4 * b + e < m)
                     out[r * m + 4 * b + e] =
-                        sum > 0.0f ? unit_exponential(ww[e]) / sum : 1.0f / (float)m;
+                        sum > 0.0f ? unit_exponential(ww[e]) * inv : 1.0f / (float)m;
         }
     }
 }
