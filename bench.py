@@ -181,6 +181,43 @@ def large_batch_leg():
             "best_index": out.best_index}
 
 
+def prior_batch_leg(P=101, steps=20):
+    """Prior-robustness batch (not part of `value`): the config-2 game and batch swept for P
+    priors in one call, against P plain sweeps of the same batch."""
+    import numpy as np
+    import torch
+    from paper_2605_18856_amd import bsse, workloads
+
+    game = workloads.game(2)
+    count = 1 << 20
+    g = bsse.bsse_create(game.m, game.n, game.K, game.A, game.B, game.prior)
+    Xd = torch.empty((count, game.m), dtype=torch.float32, device="cuda")
+    bsse.bsse_dirichlet(g, game.candidate_seed, 0, count, Xd)
+    rng = np.random.Generator(np.random.PCG64(4000))
+    pri = rng.dirichlet(np.ones(game.K), size=P)
+    pri = (pri / pri.sum(axis=1, keepdims=True)).astype(np.float32)
+    for p in range(P):          # fp32 rows whose sum is within 1e-6 of 1
+        pri[p, np.argmax(pri[p])] += np.float32(1.0 - pri[p].astype(np.float64).sum())
+    for _ in range(3):
+        bsse.bsse_sweep_priors(g, pri, Xd, count)
+        bsse.bsse_sweep(g, Xd, count)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        bsse.bsse_sweep_priors(g, pri, Xd, count)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        bsse.bsse_sweep(g, Xd, count)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    ms_batch, ms_sweep = (t1 - t0) * 1e3 / steps, (t2 - t1) * 1e3 / steps
+    return {"workload": "config2 game, 2^20 candidates, %d priors per call" % P, "priors": P,
+            "ms_per_call": ms_batch, "ms_per_plain_sweep": ms_sweep,
+            "candidate_type_prior_evals_per_s": count * game.K * P / (ms_batch * 1e-3),
+            "speedup_over_one_sweep_per_prior": P * ms_sweep / ms_batch}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +282,7 @@ def main():
                                       ("bound", "achieved", "peak", "unit", "frac", "kernel_ms")}}
         line["other_workloads"] = others
         line["large_batch_sweep_kernel"] = large_batch_leg()
+        line["prior_batch"] = prior_batch_leg()
     print(json.dumps(line), flush=True)
 
 

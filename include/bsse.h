@@ -164,6 +164,23 @@ bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_resp
 bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int64_t count,
                       float *values_dev_out, int32_t *br_dev_out);
 
+/* Prior-robustness batch: the sweep of bsse_sweep for P priors over the same game and the same
+ * candidates in one pass.  A follower's best response does not depend on the prior, so the
+ * contraction and the best responses are computed once and every prior costs K multiply-adds per
+ * candidate.  priors = host [P][K], each row checked like bsse_create's prior; 1 <= P <= 65536.
+ * res = host [P]; best_response_out = host [P][K] int32 or NULL.  For prior p the result is the
+ * greatest V_p(x_c) = sum_t priors[p][t] * l_t[j*_t(x_c)] (fp32 fused multiply-adds, t
+ * ascending), the lowest candidate index attaining it, and that candidate's best responses; the
+ * handle's own prior plays no part.  The value is the same fp32 number as a sweep of a handle
+ * created with that prior would give whenever that sweep sums its types in the same order (all
+ * paths but the small-game kernel, which adds two half sums).  n_tie_evals is the same for every
+ * prior.  Waits for the stream; its scratch (up to 1 GiB for the leader payoffs of a chunk of
+ * candidates, plus the records) is allocated on first use, grown when a later call needs more,
+ * and kept until bsse_destroy; does not touch the running best of the streamed sweep. */
+bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_dev, int64_t count,
+                              const float *priors, int P, bsse_result *res,
+                              int32_t *best_response_out);
+
 /* Which kernel family the handle uses: "valu", "mfma_f32", "mfma_bf16", "mfma_split3",
  * "mfma_split6", ... (static string). */
 const char *bsse_path_name(const bsse_game *g);

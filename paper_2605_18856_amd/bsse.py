@@ -23,7 +23,7 @@ EXPORTS = [
     "bsse_create", "bsse_create_ex", "bsse_destroy", "bsse_set_stream", "bsse_lattice",
     "bsse_lattice_count", "bsse_dirichlet", "bsse_candidates", "bsse_sweep", "bsse_sweep_reset",
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
-    "bsse_get_timing", "bsse_last_error", "bsse_status_name",
+    "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
 ]
 
 
@@ -76,6 +76,7 @@ def lib():
     L.bsse_sweep_chunk.argtypes = [vp, vp, i64, i64]
     L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
     L.bsse_eval.argtypes = [vp, vp, i64, vp, vp]
+    L.bsse_sweep_priors.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.bsse_path_name.argtypes = [vp]
     L.bsse_path_name.restype = ctypes.c_char_p
     L.bsse_set_timing.argtypes = [vp, i32]
@@ -263,6 +264,24 @@ def bsse_sweep(g: Game, candidates=None, count: Optional[int] = None) -> SweepOu
     _check(lib().bsse_sweep(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
                             ctypes.byref(res), br.ctypes.data))
     return _outcome(g, res, br)
+
+
+def bsse_sweep_priors(g: Game, priors, candidates=None, count: Optional[int] = None):
+    """priors: float32 [P][K] (host); one SweepOutcome per prior."""
+    pri = np.ascontiguousarray(priors, dtype=np.float32)
+    if pri.ndim != 2 or pri.shape[1] != g.K:
+        raise ValueError(f"priors must be [P][{g.K}]")
+    P = pri.shape[0]
+    if candidates is not None and count is None:
+        count = candidates.numel() // g.m
+    if count is None:
+        count = 0
+    res = (bsse_result * max(P, 1))()
+    br = np.full((max(P, 1), g.K), -1, dtype=np.int32)
+    _check(lib().bsse_sweep_priors(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                                   pri.ctypes.data, P, ctypes.cast(res, ctypes.c_void_p),
+                                   br.ctypes.data))
+    return [_outcome(g, res[p], br[p]) for p in range(P)]
 
 
 def bsse_sweep_reset(g: Game):

@@ -55,6 +55,23 @@ struct HostOut {            // pinned, device-visible: kernels write results her
     float fin_v;            // by the one-row re-evaluation of the winner
 };
 
+// Device scratch of the prior batch: kept by the handle and grown on demand, so that repeated
+// calls do not allocate.
+struct PriorScratch {
+    float *L = nullptr, *priors = nullptr, *blk_v = nullptr, *rows = nullptr;
+    long long *blk_i = nullptr;
+    bsse::PriorBest *run = nullptr;
+    int32_t *br = nullptr;
+    unsigned long long *ties = nullptr;
+    size_t cap_L = 0, cap_priors = 0, cap_blk_v = 0, cap_rows = 0, cap_blk_i = 0, cap_run = 0,
+           cap_br = 0, cap_ties = 0;
+    void release()
+    {
+        (void)hipFree(L); (void)hipFree(priors); (void)hipFree(blk_v); (void)hipFree(rows);
+        (void)hipFree(blk_i); (void)hipFree(run); (void)hipFree(br); (void)hipFree(ties);
+    }
+};
+
 struct bsse_game {
     int m = 0, n = 0, K = 0, storage = 0, device = 0;
     PathKind path = PATH_VALU;
@@ -75,6 +92,7 @@ struct bsse_game {
     float *best_x = nullptr;
     unsigned long long *tie_counter = nullptr;
     float *win_l = nullptr;  // [K] per-type leader payoffs of the re-evaluated winner
+    PriorScratch pri;
     // pinned host
     HostOut *h_out = nullptr;
     int32_t *h_br = nullptr;
@@ -139,6 +157,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
     (void)hipFree(g->win_l);
+    g->pri.release();
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -615,6 +634,97 @@ extern "C" bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int6
     a.X = candidates_dev; a.count = count; a.index_base = 0;
     a.V_out = values_dev_out; a.br_out = br_dev_out;
     HIP_TRY(launch_sweep(g, a, true));
+    return BSSE_OK;
+}
+
+// ------------------------------------------------------------------------ prior batch
+extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_dev, int64_t count,
+                                         const float *priors, int P, bsse_result *res,
+                                         int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!priors) return fail(BSSE_EINVAL, "priors is NULL");
+    if (!res) return fail(BSSE_EINVAL, "res is NULL");
+    if (P < 1 || P > 65536) return fail(BSSE_EINVAL, "P = %d outside 1..65536", P);
+    const int K = g->K, m = g->m;
+    for (int p = 0; p < P; ++p) {
+        double psum = 0.0;
+        for (int t = 0; t < K; ++t) {
+            const float v = priors[(size_t)p * K + t];
+            if (!std::isfinite(v)) return fail(BSSE_ENOTFINITE, "priors[%d][%d] is not finite", p, t);
+            if (v < 0.0f) return fail(BSSE_EINVAL, "priors[%d][%d] is negative", p, t);
+            psum += (double)v;
+        }
+        if (std::fabs(psum - 1.0) > 1e-6)
+            return fail(BSSE_EINVAL, "priors[%d] sums to %.9g, not 1", p, psum);
+    }
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    if (count == 0) {
+        for (int p = 0; p < P; ++p) { res[p].best_value = 0.0; res[p].best_index = -1; res[p].n_evals = 0; res[p].n_tie_evals = 0; }
+        return BSSE_OK;
+    }
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+
+    // the leader-payoff matrix is built chunk by chunk: at most 2^28 entries (1 GiB) at a time
+    long long chunk = (1LL << 28) / K;
+    if (chunk < 4096) chunk = 4096;
+    if (chunk > count) chunk = count;
+    const int nblocks = prior_batch_blocks(chunk, P);
+    PriorScratch &w = g->pri;
+    auto grow = [&](void **ptr, size_t *cap, size_t bytes) -> bsse_status {
+        if (bytes <= *cap) return BSSE_OK;
+        HIP_TRY(hipStreamSynchronize(g->stream));      // nothing enqueued may still use the old block
+        (void)hipFree(*ptr);
+        *ptr = nullptr; *cap = 0;
+        HIP_TRY(hipMalloc(ptr, bytes));
+        *cap = bytes;
+        return BSSE_OK;
+    };
+    if ((st = grow((void **)&w.L, &w.cap_L, (size_t)chunk * K * sizeof(float))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.priors, &w.cap_priors, (size_t)P * K * sizeof(float))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.blk_v, &w.cap_blk_v, (size_t)nblocks * P * sizeof(float))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.blk_i, &w.cap_blk_i, (size_t)nblocks * P * sizeof(long long))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.run, &w.cap_run, (size_t)P * sizeof(PriorBest))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.rows, &w.cap_rows, (size_t)P * m * sizeof(float))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.br, &w.cap_br, (size_t)P * K * sizeof(int32_t))) != BSSE_OK) return st;
+    if ((st = grow((void **)&w.ties, &w.cap_ties, sizeof(unsigned long long))) != BSSE_OK) return st;
+    HIP_TRY(hipMemcpyAsync(w.priors, priors, (size_t)P * K * sizeof(float), hipMemcpyHostToDevice, g->stream));
+    HIP_TRY(hipMemsetAsync(w.ties, 0, sizeof(unsigned long long), g->stream));   // a counter of its own
+    HIP_TRY(hipStreamSynchronize(g->stream));          // the host array is the caller's again
+    for (long long base = 0; base < count; base += chunk) {
+        const long long rows = count - base < chunk ? count - base : chunk;
+        SweepArgs a{};
+        a.X = candidates_dev + base * m; a.count = rows; a.index_base = base;
+        a.l_out = w.L; a.tie_counter = w.ties;
+        HIP_TRY(launch_sweep(g, a, true));
+        HIP_TRY(launch_prior_batch(w.L, rows, base, K, w.priors, P, base == 0 ? 1 : 0, w.blk_v, w.blk_i,
+                                   w.run, g->stream));
+    }
+    unsigned long long ties = 0;
+    HIP_TRY(hipMemcpyAsync(&ties, w.ties, sizeof(ties), hipMemcpyDeviceToHost, g->stream));
+    // best responses of the P winners: their rows, evaluated once more with per-candidate outputs
+    HIP_TRY(launch_gather_rows(candidates_dev, w.run, P, m, w.rows, g->stream));
+    {
+        SweepArgs a{};
+        a.X = w.rows; a.count = P; a.index_base = 0; a.br_out = w.br;
+        HIP_TRY(launch_sweep(g, a, true));
+    }
+    std::vector<PriorBest> run((size_t)P);
+    std::vector<int32_t> br(best_response_out ? (size_t)P * K : 0);
+    HIP_TRY(hipMemcpyAsync(run.data(), w.run, (size_t)P * sizeof(PriorBest), hipMemcpyDeviceToHost, g->stream));
+    if (best_response_out)
+        HIP_TRY(hipMemcpyAsync(br.data(), w.br, (size_t)P * K * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    for (int p = 0; p < P; ++p) {
+        res[p].best_value = run[p].has ? (double)run[p].value : 0.0;
+        res[p].best_index = run[p].has ? (int64_t)run[p].index : -1;
+        res[p].n_evals = (int64_t)count * K;
+        res[p].n_tie_evals = (int64_t)ties;
+    }
+    if (best_response_out) memcpy(best_response_out, br.data(), br.size() * sizeof(int32_t));
     return BSSE_OK;
 }
 

@@ -32,11 +32,11 @@ struct SweepArgs {
     float *blk_v;            // [nblocks]          (sweep mode)
     long long *blk_i;        // [nblocks] global candidate index, LLONG_MAX if none
     unsigned long long *tie_counter;  // += number of (candidate,type) evaluations with a tie
-    // Type-sliced evaluation (general matrix-core kernel only, evaluation mode): when l_out is set
-    // the launch is split over the types as well, each workgroup writes the leader payoffs
-    // l_t[j*_t] of its slice of types to l_out [count][K], and a second kernel forms V_out from
-    // them in type order (the same sum, term by term, as the unsliced kernel).  For a handful of
-    // rows against many types, where one workgroup walking every type would leave the chip idle.
+    // Evaluation mode only: l_out [count][K] receives the leader payoffs l_t[j*_t] at the best
+    // responses.  In the general matrix-core kernel this selects the type-sliced instantiation:
+    // for a handful of rows the launch is split over the types as well (one workgroup walking
+    // every type would leave the chip idle), and a second kernel forms V_out from l_out in type
+    // order (the same sum, term by term, as the unsliced kernel).
     float *l_out;
     int slice_stages;        // LDS stages per slice (set by the launcher)
 };
@@ -59,6 +59,13 @@ struct FinishArgs {
     float *best_x;           // [m] row of the running best
     float *win_v;            // value of the re-evaluated row (pinned host)
     int32_t *win_br;         // [K] its best responses (pinned host)
+};
+
+// Running best of one prior of a prior batch.
+struct PriorBest {
+    float value;
+    int   has;
+    long long index;
 };
 
 enum PathKind { PATH_VALU = 1, PATH_MFMA_F32 = 2, PATH_MFMA_BF16 = 3, PATH_MFMA_SPLIT = 4 };
@@ -97,6 +104,16 @@ hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long 
                                const float *X, long long index_base, int m, int first,
                                unsigned long long *tie_counter, RunningBest *run,
                                RunningBest *run_host, float *best_x, hipStream_t s);
+
+// Prior batch (see prior_batch.hip): V_p[c] = sum_t priors[p][t] * L[c][t] and the arg-max over c
+// for each of P priors, merged into run[P] (first != 0: replaced).  blk_v / blk_i: workspace of
+// prior_batch_blocks(count, P) * P records.
+int prior_batch_blocks(long long count, int P);
+hipError_t launch_prior_batch(const float *L, long long count, long long index_base, int K,
+                              const float *priors_dev, int P, int first, float *blk_v,
+                              long long *blk_i, PriorBest *run, hipStream_t s);
+hipError_t launch_gather_rows(const float *X, const PriorBest *run, int P, int m, float *rows,
+                              hipStream_t s);
 
 hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
                           float *out, hipStream_t s);

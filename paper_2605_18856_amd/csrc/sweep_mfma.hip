@@ -697,11 +697,11 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
         return hipGetLastError();
     }
-    // type-sliced evaluation: 32 candidates per wavefront, whole groups per slice, about kSlices
-    // slices
+    // type-sliced evaluation: 32 candidates per wavefront, whole groups per slice; few rows are
+    // cut into about 256 slices, many rows fill the chip by themselves
     const long long per = 32LL * v->waves, blocks = (a.count + per - 1) / per;
-    if (a.blk_v || blocks > 65535) return hipErrorInvalidValue;
-    constexpr int kSlices = 256;
+    if (a.blk_v || blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    const int kSlices = blocks >= 256 ? 1 : (int)(256 / blocks);
     const int spg = v->geo.tpg > v->stage_tiles ? v->geo.tpg / v->stage_tiles : 1;   // stages per group
     SweepArgs b = a;
     b.slice_stages = ((nstages + kSlices - 1) / kSlices + spg - 1) / spg * spg;

@@ -194,6 +194,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                     if (EVAL) {
                         const unsigned c = task * per_iter + ct * 32 + col;
                         if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx[ct][tl];
+                        if (a.l_out && c < count) a.l_out[(size_t)c * K + 4 * T + 2 * h + tl] = l[ct][tl];
                     }
                 }
         }

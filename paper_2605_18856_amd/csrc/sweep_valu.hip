@@ -110,6 +110,7 @@ __global__ void __launch_bounds__(WG) sweep_valu_kernel(GameView g, SweepArgs a)
         V = fmaf(g.prior[t], best_l, V);
         ties += tied ? 1u : 0u;
         if (EVAL && valid && a.br_out) a.br_out[c * K + t] = best_j;
+        if (EVAL && valid && a.l_out) a.l_out[c * K + t] = best_l;
     }
     if (!(V == V)) V = -INFINITY;                  // NaN never wins
 
