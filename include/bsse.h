@@ -181,6 +181,38 @@ bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_dev, int64_t
                               const float *priors, int P, bsse_result *res,
                               int32_t *best_response_out);
 
+/* LP polish.  The sweep only sees its candidates; the linear program of the winner's best-response
+ * profile lands on the exact vertex of that profile's region (one program of the multiple-LPs
+ * characterisation of the strong Stackelberg equilibrium):
+ *     maximise   sum_t prior[t] * x . A_t[:, j_t]
+ *     subject to x . (B_t[:, j_t] - B_t[:, j']) >= 0  for every t and j' != j_t,  x on the simplex.
+ *
+ * bsse_profile_lp: host only, no device needed.  Solves that program in fp64 (simplex method on
+ * the dual, whose tableau has m rows) for the game given by host arrays laid out as for
+ * bsse_create (prior: finite, >= 0; its sum is not checked) and profile = host [K] actions.
+ * *feasible_out = 1 and x_out (host [m], on the simplex), *value_out filled; or *feasible_out = 0
+ * when the profile is a best response to no x (x_out, value_out untouched).  BSSE_EOVERFLOW when
+ * m * (2 + K(n-1) + m) exceeds 2^28, BSSE_ESTATE if the method does not converge.
+ *
+ * bsse_polish: polishes the result of the last completed sweep of the handle (BSSE_ESTATE if
+ * none).  profile = host [K], or NULL for the winner's own best responses.  Solves the program
+ * with the payoffs as given to create (fp32, also for BF16 storage), then evaluates, with the
+ * sweep's own kernels, eight points of the segment from the program's vertex to the sweep's
+ * winner (the vertex lies on the boundary of the profile's region, where rounding x to fp32 can
+ * tip a follower over to another action; V is linear along the segment inside the region) and
+ * keeps the best: x_out (host [m] fp32), res->best_value = its V as the kernels compute it,
+ * res->best_index = which point (0 = the vertex ... 7 = the sweep's winner), best_response_out
+ * (host [K], may be NULL) its best responses, *lp_value_out (may be NULL) the program's optimum.
+ * Then  V(sweep's winner) <= res->best_value <= equilibrium value, and *lp_value_out is the most
+ * any commitment with that profile can earn (the equilibrium value itself when the profile is
+ * the equilibrium's).  BSSE_EINVAL if the given profile is a best response nowhere.  Waits for
+ * the stream. */
+bsse_status bsse_profile_lp(int m, int n, int K, const float *A, const float *B, const float *prior,
+                            const int32_t *profile, double *x_out, double *value_out,
+                            int *feasible_out);
+bsse_status bsse_polish(bsse_game *g, const int32_t *profile, float *x_out, bsse_result *res,
+                        int32_t *best_response_out, double *lp_value_out);
+
 /* Which kernel family the handle uses: "valu", "mfma_f32", "mfma_bf16", "mfma_split3",
  * "mfma_split6", ... (static string). */
 const char *bsse_path_name(const bsse_game *g);

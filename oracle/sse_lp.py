@@ -43,6 +43,29 @@ def solve(A, B, prior):
     return best
 
 
+def profile_lp(A, B, prior, profile):
+    """The linear program of ONE follower profile: (feasible, value, x).  Same program as one
+    pass of the loop in ``solve`` (kept apart so that a single profile can be checked)."""
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    p = np.asarray(prior, dtype=np.float64)
+    K, m, n = A.shape
+    c = np.zeros(m)
+    rows = []
+    for t, j in enumerate(profile):
+        c -= p[t] * A[t][:, j]
+        for jp in range(n):
+            if jp != j:
+                rows.append(B[t][:, jp] - B[t][:, j])
+    A_ub = np.asarray(rows) if rows else None
+    b_ub = np.zeros(len(rows)) if rows else None
+    res = linprog(c, A_ub=A_ub, b_ub=b_ub, A_eq=np.ones((1, m)), b_eq=[1.0],
+                  bounds=[(0, None)] * m, method="highs")
+    if res.status != 0:
+        return False, None, None
+    return True, -res.fun, res.x.copy()
+
+
 def maximin(A):
     """Value and strategy of the row player's maximin LP for matrix A (m x n):
     max v s.t. x.A[:, j] >= v for all j, x in the simplex."""

@@ -24,6 +24,7 @@ EXPORTS = [
     "bsse_lattice_count", "bsse_dirichlet", "bsse_candidates", "bsse_sweep", "bsse_sweep_reset",
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
+    "bsse_profile_lp", "bsse_polish",
 ]
 
 
@@ -77,6 +78,8 @@ def lib():
     L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
     L.bsse_eval.argtypes = [vp, vp, i64, vp, vp]
     L.bsse_sweep_priors.argtypes = [vp, vp, i64, vp, i32, vp, vp]
+    L.bsse_profile_lp.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, P(ctypes.c_double), P(i32)]
+    L.bsse_polish.argtypes = [vp, vp, vp, P(bsse_result), vp, P(ctypes.c_double)]
     L.bsse_path_name.argtypes = [vp]
     L.bsse_path_name.restype = ctypes.c_char_p
     L.bsse_set_timing.argtypes = [vp, i32]
@@ -282,6 +285,43 @@ def bsse_sweep_priors(g: Game, priors, candidates=None, count: Optional[int] = N
                                    pri.ctypes.data, P, ctypes.cast(res, ctypes.c_void_p),
                                    br.ctypes.data))
     return [_outcome(g, res[p], br[p]) for p in range(P)]
+
+
+def bsse_profile_lp(A, B, prior, profile):
+    """Host-only: (feasible, value, x float64 [m]) of the linear program of one follower profile."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    pr = np.ascontiguousarray(prior, dtype=np.float32)
+    prof = np.ascontiguousarray(profile, dtype=np.int32)
+    K, m, n = A.shape
+    if B.shape != A.shape or pr.shape != (K,) or prof.shape != (K,):
+        raise ValueError("A, B: [K][m][n]; prior, profile: [K]")
+    x = np.zeros(m, dtype=np.float64)
+    v, ok = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().bsse_profile_lp(m, n, K, A.ctypes.data, B.ctypes.data, pr.ctypes.data,
+                                 prof.ctypes.data, x.ctypes.data, ctypes.byref(v), ctypes.byref(ok)))
+    return bool(ok.value), (v.value if ok.value else None), (x if ok.value else None)
+
+
+@dataclass
+class PolishOutcome:
+    x: np.ndarray                  # float32 [m]: the polished commitment
+    value: float                   # its V as the sweep kernels compute it
+    point: int                     # 0 = the program's vertex ... 7 = the sweep's own winner
+    best_response: np.ndarray      # int32 [K]
+    lp_value: float                # optimum of the profile's linear program
+
+
+def bsse_polish(g: Game, profile=None) -> PolishOutcome:
+    prof = None if profile is None else np.ascontiguousarray(profile, dtype=np.int32)
+    if prof is not None and prof.shape != (g.K,):
+        raise ValueError(f"profile must be [{g.K}]")
+    x = np.zeros(g.m, dtype=np.float32)
+    br = np.full(g.K, -1, dtype=np.int32)
+    res, lp = bsse_result(), ctypes.c_double(0.0)
+    _check(lib().bsse_polish(g.handle, None if prof is None else prof.ctypes.data, x.ctypes.data,
+                             ctypes.byref(res), br.ctypes.data, ctypes.byref(lp)))
+    return PolishOutcome(x, res.best_value, int(res.best_index), br, lp.value)
 
 
 def bsse_sweep_reset(g: Game):

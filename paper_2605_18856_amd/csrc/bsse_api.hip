@@ -93,6 +93,10 @@ struct bsse_game {
     unsigned long long *tie_counter = nullptr;
     float *win_l = nullptr;  // [K] per-type leader payoffs of the re-evaluated winner
     PriorScratch pri;
+    // host copies of the game as given to create (fp32, unrounded): the profile LP of bsse_polish
+    std::vector<float> hA, hB, hprior;
+    float *pol_rows = nullptr, *pol_v = nullptr;   // device scratch of bsse_polish
+    int32_t *pol_br = nullptr;
     // pinned host
     HostOut *h_out = nullptr;
     int32_t *h_br = nullptr;
@@ -158,6 +162,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
     (void)hipFree(g->win_l);
     g->pri.release();
+    (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -316,6 +321,9 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
     if (!g) return fail(BSSE_ENOMEM, "host allocation failed");
     g->m = m; g->n = n; g->K = K; g->storage = opt->storage; g->device = dev;
     g->path = path;
+    try {
+        g->hA.assign(A, A + elems); g->hB.assign(B, B + elems); g->hprior.assign(prior, prior + K);
+    } catch (...) { delete g; return fail(BSSE_ENOMEM, "host allocation failed"); }
     g->view.variant = variant;
 
     DeviceGuard dg(dev);
@@ -725,6 +733,118 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
         res[p].n_tie_evals = (int64_t)ties;
     }
     if (best_response_out) memcpy(best_response_out, br.data(), br.size() * sizeof(int32_t));
+    return BSSE_OK;
+}
+
+// ----------------------------------------------------------------------------- LP polish
+namespace {
+
+bsse_status check_profile(int n, int K, const int32_t *profile)
+{
+    for (int t = 0; t < K; ++t)
+        if (profile[t] < 0 || profile[t] >= n)
+            return fail(BSSE_EINVAL, "profile[%d] = %d outside 0..%d", t, (int)profile[t], n - 1);
+    return BSSE_OK;
+}
+
+constexpr int kPolishRows = 8;       // segment points evaluated by bsse_polish
+
+}  // namespace
+
+extern "C" bsse_status bsse_profile_lp(int m, int n, int K, const float *A, const float *B,
+                                       const float *prior, const int32_t *profile, double *x_out,
+                                       double *value_out, int *feasible_out)
+{
+    g_err[0] = 0;
+    if (m < 1 || n < 1 || K < 1 || m > 4096 || n > 65535 || K > 65535)
+        return fail(BSSE_EINVAL, "bad dimensions m=%d n=%d K=%d", m, n, K);
+    if (!A || !B || !prior || !profile || !x_out || !value_out || !feasible_out)
+        return fail(BSSE_EINVAL, "NULL argument");
+    // the dual tableau holds m rows of 2 + K(n-1) + m columns
+    const double cells = (double)m * (2.0 + (double)K * (n - 1) + m);
+    if (cells > (double)(1u << 28)) return fail(BSSE_EOVERFLOW, "the program's tableau (%.3g cells) is too large", cells);
+    bsse_status st = check_profile(n, K, profile);
+    if (st != BSSE_OK) return st;
+    const size_t elems = (size_t)K * m * n;
+    for (size_t e = 0; e < elems; ++e)
+        if (!std::isfinite(A[e]) || !std::isfinite(B[e]))
+            return fail(BSSE_ENOTFINITE, "payoff entry %zu is not finite", e);
+    for (int t = 0; t < K; ++t)
+        if (!std::isfinite(prior[t]) || prior[t] < 0.0f)
+            return fail(std::isfinite(prior[t]) ? BSSE_EINVAL : BSSE_ENOTFINITE, "bad prior[%d]", t);
+    std::vector<double> x;
+    try { x.resize((size_t)m); } catch (...) { return fail(BSSE_ENOMEM, "host allocation failed"); }
+    double v = 0.0;
+    int rc;
+    try { rc = solve_profile_lp(m, n, K, A, B, prior, profile, x.data(), &v); }
+    catch (...) { return fail(BSSE_ENOMEM, "host allocation failed"); }
+    if (rc == 2) return fail(BSSE_ESTATE, "the simplex method did not converge");
+    if (rc == 0) { memcpy(x_out, x.data(), (size_t)m * sizeof(double)); *value_out = v; }
+    *feasible_out = rc == 0 ? 1 : 0;
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_polish(bsse_game *g, const int32_t *profile, float *x_out,
+                                   bsse_result *res, int32_t *best_response_out,
+                                   double *lp_value_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!x_out || !res) return fail(BSSE_EINVAL, "NULL argument");
+    if (g->fresh || !g->h_out || !g->h_out->run.has)
+        return fail(BSSE_ESTATE, "no sweep result to polish: call bsse_sweep (or _chunk and _result) first");
+    const int m = g->m, n = g->n, K = g->K;
+    if (profile) {
+        bsse_status st = check_profile(n, K, profile);
+        if (st != BSSE_OK) return st;
+    }
+    const double cells = (double)m * (2.0 + (double)K * (n - 1) + m);
+    if (cells > (double)(1u << 28)) return fail(BSSE_EOVERFLOW, "the program's tableau (%.3g cells) is too large", cells);
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    HIP_TRY(hipStreamSynchronize(g->stream));            // the winner's row and profile are final
+    std::vector<int32_t> prof((size_t)K);
+    std::vector<float> start((size_t)m), rows((size_t)kPolishRows * m), vals((size_t)kPolishRows);
+    std::vector<int32_t> brs((size_t)kPolishRows * K);
+    std::vector<double> x((size_t)m);
+    memcpy(prof.data(), profile ? profile : g->h_br, (size_t)K * sizeof(int32_t));
+    HIP_TRY(hipMemcpy(start.data(), g->best_x, (size_t)m * sizeof(float), hipMemcpyDeviceToHost));
+    double v_lp = 0.0;
+    const int rc = solve_profile_lp(m, n, K, g->hA.data(), g->hB.data(), g->hprior.data(), prof.data(),
+                                    x.data(), &v_lp);
+    if (rc == 2) return fail(BSSE_ESTATE, "the simplex method did not converge");
+    if (rc == 1) return fail(BSSE_EINVAL, "the profile is a best response nowhere on the simplex");
+    // the segment from the program's vertex to the sweep's winner: the vertex sits on the boundary
+    // of the profile's region, where fp32 rounding of x can tip a follower over to another action;
+    // V is linear along the segment inside the region, so the best evaluated point is kept
+    static const double eps[kPolishRows] = { 0.0, 0x1p-22, 0x1p-19, 0x1p-16, 0x1p-13, 0x1p-10, 0x1p-6, 1.0 };
+    for (int e = 0; e < kPolishRows; ++e)
+        for (int i = 0; i < m; ++i)
+            rows[(size_t)e * m + i] = (float)((1.0 - eps[e]) * x[i] + eps[e] * (double)start[i]);
+    if (!g->pol_rows) {
+        // a row stride of m floats keeps 16-byte alignment whenever m % 4 == 0, as the kernels ask
+        HIP_TRY(hipMalloc((void **)&g->pol_rows, (size_t)kPolishRows * m * sizeof(float)));
+        HIP_TRY(hipMalloc((void **)&g->pol_v, (size_t)kPolishRows * sizeof(float)));
+        HIP_TRY(hipMalloc((void **)&g->pol_br, (size_t)kPolishRows * K * sizeof(int32_t)));
+    }
+    HIP_TRY(hipMemcpyAsync(g->pol_rows, rows.data(), rows.size() * sizeof(float), hipMemcpyHostToDevice, g->stream));
+    SweepArgs a{};
+    a.X = g->pol_rows; a.count = kPolishRows; a.index_base = 0;
+    a.V_out = g->pol_v; a.br_out = g->pol_br;
+    HIP_TRY(launch_sweep(g, a, true));
+    HIP_TRY(hipMemcpyAsync(vals.data(), g->pol_v, vals.size() * sizeof(float), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(brs.data(), g->pol_br, brs.size() * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    int best = kPolishRows - 1;                          // the sweep's own winner, unless a point beats it
+    for (int e = kPolishRows - 2; e >= 0; --e)
+        if (vals[e] >= vals[best]) best = e;             // equal values: the point nearest the vertex
+    memcpy(x_out, &rows[(size_t)best * m], (size_t)m * sizeof(float));
+    res->best_value = (double)vals[best];
+    res->best_index = best;
+    res->n_evals = (int64_t)kPolishRows * K;
+    res->n_tie_evals = 0;
+    if (best_response_out) memcpy(best_response_out, &brs[(size_t)best * K], (size_t)K * sizeof(int32_t));
+    if (lp_value_out) *lp_value_out = v_lp;
     return BSSE_OK;
 }
 

@@ -115,6 +115,12 @@ hipError_t launch_prior_batch(const float *L, long long count, long long index_b
 hipError_t launch_gather_rows(const float *X, const PriorBest *run, int P, int m, float *rows,
                               hipStream_t s);
 
+// Host code: the linear program of one pure follower profile (see profile_lp.hip).  Returns 0 with
+// x_out[m] (on the simplex) and *value_out, 1 when the profile is a best response nowhere, 2 when
+// the simplex method hit its iteration limit.  May throw std::bad_alloc.
+int solve_profile_lp(int m, int n, int K, const float *A, const float *B, const float *prior,
+                     const int32_t *profile, double *x_out, double *value_out);
+
 hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
                           float *out, hipStream_t s);
 hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m, float *out,
