@@ -131,6 +131,18 @@ bsse_status bsse_lattice_count(int m, int N, int64_t *count_out);
 bsse_status bsse_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
                            float *out_dev);
 
+/* Local sets for refinement around a survivor of a sweep: the same generators with every point t
+ * replaced by the convex combination (1 - radius) * centre + radius * t, i.e. the simplex (and
+ * the set on it) shrunk by `radius` towards `centre`; component i is computed as
+ * fl32(fl32(radius * t_i) + fl32(fl32(1 - radius) * centre[i])) (three separately rounded fp32
+ * operations).  centre = host [m], finite (a point of the simplex keeps the set on the simplex;
+ * not checked); 0 <= radius <= 1 (1 = the plain set, 0 = the centre repeated).  Otherwise as
+ * bsse_lattice / bsse_dirichlet. */
+bsse_status bsse_lattice_around(bsse_game *g, int N, const float *centre, float radius,
+                                int64_t *count_out);
+bsse_status bsse_dirichlet_around(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
+                                  const float *centre, float radius, float *out_dev);
+
 /* The handle-owned generated set: *dev_out = device pointer ([*count_out][m] fp32),
  * valid until the next generation call or destroy.  BSSE_ESTATE if none. */
 bsse_status bsse_candidates(bsse_game *g, const float **dev_out, int64_t *count_out);
@@ -180,6 +192,17 @@ bsse_status bsse_eval(bsse_game *g, const float *candidates_dev, int64_t count,
 bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_dev, int64_t count,
                               const float *priors, int P, bsse_result *res,
                               int32_t *best_response_out);
+
+/* Top-k: the k best candidates of the sweep instead of the best one, in the order "greater V
+ * first, lower index among equal values" (so entry 0 is bsse_sweep's answer).  1 <= k <= 256.
+ * values_out = host [k] (the kernels' fp32 values, widened), indices_out = host [k],
+ * best_response_out = host [k][K] int32 or NULL; *found_out = min(k, count) entries are written.
+ * The handle's prior is used.  Waits for the stream; allocates scratch (4 bytes per candidate of
+ * a chunk of at most 2^26, plus records) for the duration of the call; does not touch the
+ * running best of the streamed sweep. */
+bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev, int64_t count, int k,
+                            double *values_out, int64_t *indices_out, int32_t *best_response_out,
+                            int *found_out);
 
 /* LP polish.  The sweep only sees its candidates; the linear program of the winner's best-response
  * profile lands on the exact vertex of that profile's region (one program of the multiple-LPs

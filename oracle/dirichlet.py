@@ -66,3 +66,12 @@ def rows(seed: int, first: int, count: int, m: int) -> np.ndarray:
         s = s + g[:, i]
     out = np.where(s[:, None] > 0, g / np.where(s > 0, s, 1.0)[:, None], 1.0 / m)
     return out
+
+
+def rows_around(seed: int, first: int, count: int, m: int, centre, radius) -> np.ndarray:
+    """``rows`` shrunk towards `centre`: (1 - radius) * centre + radius * row, in float64 (radius and
+    1 - radius taken as the float32 numbers the library uses)."""
+    r = np.float64(np.float32(radius))
+    omr = np.float64(np.float32(np.float32(1.0) - np.float32(radius)))
+    c = np.asarray(centre, dtype=np.float32).astype(np.float64)
+    return r * rows(seed, first, count, m) + omr * c[None, :]

@@ -75,3 +75,14 @@ def points_f32(m: int, N: int, first: int = 0, cnt: int = None) -> np.ndarray:
     k = np.asarray([unrank(r, m, N) for r in range(first, first + cnt)],
                    dtype=np.int64).reshape(-1, m)
     return (k.astype(np.float32) / np.float32(N)).astype(np.float32)
+
+
+def points_around_f32(m: int, N: int, centre, radius, first: int = 0, cnt: int = None) -> np.ndarray:
+    """The lattice shrunk towards `centre`: every point t of ``points_f32`` becomes
+    (1 - radius) * centre + radius * t, each component as three separately rounded float32
+    operations fl(fl(radius * t) + fl(fl(1 - radius) * centre))."""
+    t = points_f32(m, N, first, cnt)
+    r = np.float32(radius)
+    omr = np.float32(np.float32(1.0) - r)
+    c = np.asarray(centre, dtype=np.float32)
+    return ((r * t).astype(np.float32) + (omr * c).astype(np.float32)[None, :]).astype(np.float32)

@@ -24,7 +24,8 @@ EXPORTS = [
     "bsse_lattice_count", "bsse_dirichlet", "bsse_candidates", "bsse_sweep", "bsse_sweep_reset",
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
-    "bsse_profile_lp", "bsse_polish",
+    "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
+    "bsse_dirichlet_around",
 ]
 
 
@@ -80,6 +81,9 @@ def lib():
     L.bsse_sweep_priors.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.bsse_profile_lp.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, P(ctypes.c_double), P(i32)]
     L.bsse_polish.argtypes = [vp, vp, vp, P(bsse_result), vp, P(ctypes.c_double)]
+    L.bsse_sweep_topk.argtypes = [vp, vp, i64, i32, vp, vp, vp, P(i32)]
+    L.bsse_lattice_around.argtypes = [vp, i32, vp, ctypes.c_float, P(i64)]
+    L.bsse_dirichlet_around.argtypes = [vp, u64, i64, i64, vp, ctypes.c_float, vp]
     L.bsse_path_name.argtypes = [vp]
     L.bsse_path_name.restype = ctypes.c_char_p
     L.bsse_set_timing.argtypes = [vp, i32]
@@ -217,6 +221,25 @@ def bsse_dirichlet(g: Game, seed: int, first: int, count: int, out=None):
                                 _dev_ptr(out, "float32", count * g.m)))
 
 
+def _centre(g, centre):
+    c = np.ascontiguousarray(centre, dtype=np.float32)
+    if c.shape != (g.m,):
+        raise ValueError(f"centre must be [{g.m}]")
+    return c
+
+
+def bsse_lattice_around(g: Game, N: int, centre, radius: float) -> int:
+    c, ctr = ctypes.c_int64(), _centre(g, centre)
+    _check(lib().bsse_lattice_around(g.handle, N, ctr.ctypes.data, float(radius), ctypes.byref(c)))
+    return c.value
+
+
+def bsse_dirichlet_around(g: Game, seed: int, first: int, count: int, centre, radius: float, out=None):
+    ctr = _centre(g, centre)
+    _check(lib().bsse_dirichlet_around(g.handle, ctypes.c_uint64(seed), first, count, ctr.ctypes.data,
+                                       float(radius), _dev_ptr(out, "float32", count * g.m)))
+
+
 def bsse_candidates(g: Game):
     """(device pointer, count) of the handle-owned generated set."""
     p, c = ctypes.c_void_p(), ctypes.c_int64()
@@ -285,6 +308,24 @@ def bsse_sweep_priors(g: Game, priors, candidates=None, count: Optional[int] = N
                                    pri.ctypes.data, P, ctypes.cast(res, ctypes.c_void_p),
                                    br.ctypes.data))
     return [_outcome(g, res[p], br[p]) for p in range(P)]
+
+
+def bsse_sweep_topk(g: Game, k: int, candidates=None, count: Optional[int] = None):
+    """(values float64 [f], indices int64 [f], best responses int32 [f][K]) of the f = min(k, count)
+    best candidates, best first."""
+    if candidates is not None and count is None:
+        count = candidates.numel() // g.m
+    if count is None:
+        count = 0
+    kk = max(int(k), 1)
+    v = np.zeros(kk, dtype=np.float64)
+    idx = np.full(kk, -1, dtype=np.int64)
+    br = np.full((kk, g.K), -1, dtype=np.int32)
+    found = ctypes.c_int(0)
+    _check(lib().bsse_sweep_topk(g.handle, _dev_ptr(candidates, "float32", count * g.m), count, int(k),
+                                 v.ctypes.data, idx.ctypes.data, br.ctypes.data, ctypes.byref(found)))
+    f = found.value
+    return v[:f].copy(), idx[:f].copy(), br[:f].copy()
 
 
 def bsse_profile_lp(A, B, prior, profile):

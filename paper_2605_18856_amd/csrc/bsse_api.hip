@@ -95,6 +95,7 @@ struct bsse_game {
     PriorScratch pri;
     // host copies of the game as given to create (fp32, unrounded): the profile LP of bsse_polish
     std::vector<float> hA, hB, hprior;
+    float *centre_dev = nullptr;                   // [m] centre of a local candidate set
     float *pol_rows = nullptr, *pol_v = nullptr;   // device scratch of bsse_polish
     int32_t *pol_br = nullptr;
     // pinned host
@@ -163,6 +164,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->win_l);
     g->pri.release();
     (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
+    (void)hipFree(g->centre_dev);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -429,11 +431,53 @@ extern "C" bsse_status bsse_lattice_count(int m, int N, int64_t *count_out)
     return BSSE_OK;
 }
 
+namespace {
+
+// centre (host [m]) and radius of a local set: validated, the centre uploaded to the handle
+bsse_status check_around(const bsse_game *g, const float *centre, float radius)
+{
+    if (!centre) return fail(BSSE_EINVAL, "centre is NULL");
+    if (!(radius >= 0.0f && radius <= 1.0f)) return fail(BSSE_EINVAL, "radius %g outside 0..1", (double)radius);
+    for (int i = 0; i < g->m; ++i)
+        if (!std::isfinite(centre[i])) return fail(BSSE_ENOTFINITE, "centre[%d] is not finite", i);
+    return BSSE_OK;
+}
+
+bsse_status upload_centre(bsse_game *g, const float *centre)
+{
+    if (!g->centre_dev) HIP_TRY(hipMalloc((void **)&g->centre_dev, (size_t)g->m * sizeof(float)));
+    HIP_TRY(hipMemcpyAsync(g->centre_dev, centre, (size_t)g->m * sizeof(float), hipMemcpyHostToDevice, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));          // the host array is the caller's again
+    return BSSE_OK;
+}
+
+bsse_status lattice_impl(bsse_game *g, int N, const float *centre, float radius, int64_t *count_out);
+
+}  // namespace
+
 extern "C" bsse_status bsse_lattice(bsse_game *g, int N, int64_t *count_out)
 {
     g_err[0] = 0;
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
     if (!count_out) return fail(BSSE_EINVAL, "count_out is NULL");
+    return lattice_impl(g, N, nullptr, 1.0f, count_out);
+}
+
+extern "C" bsse_status bsse_lattice_around(bsse_game *g, int N, const float *centre, float radius,
+                                           int64_t *count_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!count_out) return fail(BSSE_EINVAL, "count_out is NULL");
+    bsse_status st = check_around(g, centre, radius);
+    if (st != BSSE_OK) return st;
+    return lattice_impl(g, N, centre, radius, count_out);
+}
+
+namespace {
+
+bsse_status lattice_impl(bsse_game *g, int N, const float *centre, float radius, int64_t *count_out)
+{
     int64_t cnt = 0;
     bsse_status st = bsse_lattice_count(g->m, N, &cnt);
     if (st != BSSE_OK) return st;
@@ -461,17 +505,41 @@ extern "C" bsse_status bsse_lattice(bsse_game *g, int N, int64_t *count_out)
     }
     HIP_TRY(hipMemcpyAsync(g->lat_table, tab.data(), tab_elems * 8, hipMemcpyHostToDevice, g->stream));
     HIP_TRY(hipStreamSynchronize(g->stream));     // `tab` is pageable and dies with this frame
-    HIP_TRY(launch_lattice(g->lat_table, m, N, cnt, g->gen, g->stream));
+    if (centre && (st = upload_centre(g, centre)) != BSSE_OK) return st;
+    HIP_TRY(launch_lattice(g->lat_table, m, N, cnt, centre ? g->centre_dev : nullptr, radius, g->gen, g->stream));
     g->gen_count = cnt;
     *count_out = cnt;
     return BSSE_OK;
 }
+
+bsse_status dirichlet_impl(bsse_game *g, uint64_t seed, int64_t first, int64_t count, const float *centre,
+                           float radius, float *out_dev);
+
+}  // namespace
 
 extern "C" bsse_status bsse_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
                                       float *out_dev)
 {
     g_err[0] = 0;
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    return dirichlet_impl(g, seed, first, count, nullptr, 1.0f, out_dev);
+}
+
+extern "C" bsse_status bsse_dirichlet_around(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
+                                             const float *centre, float radius, float *out_dev)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    bsse_status st = check_around(g, centre, radius);
+    if (st != BSSE_OK) return st;
+    return dirichlet_impl(g, seed, first, count, centre, radius, out_dev);
+}
+
+namespace {
+
+bsse_status dirichlet_impl(bsse_game *g, uint64_t seed, int64_t first, int64_t count, const float *centre,
+                           float radius, float *out_dev)
+{
     if (first < 0 || count < 0) return fail(BSSE_EINVAL, "first and count must be >= 0");
     if (count > CHUNK_MAX) return fail(BSSE_EOVERFLOW, "count exceeds 2^31 rows per call");
     if (first > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "first + count overflows");
@@ -483,10 +551,16 @@ extern "C" bsse_status bsse_dirichlet(bsse_game *g, uint64_t seed, int64_t first
         if (st != BSSE_OK) return st;
         dst = g->gen;
     }
-    HIP_TRY(launch_dirichlet(seed, first, count, g->m, dst, g->stream));
+    if (centre) {
+        bsse_status st = upload_centre(g, centre);
+        if (st != BSSE_OK) return st;
+    }
+    HIP_TRY(launch_dirichlet(seed, first, count, g->m, centre ? g->centre_dev : nullptr, radius, dst, g->stream));
     if (!out_dev) g->gen_count = count;
     return BSSE_OK;
 }
+
+}  // namespace
 
 extern "C" bsse_status bsse_candidates(bsse_game *g, const float **dev_out, int64_t *count_out)
 {
@@ -733,6 +807,98 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
         res[p].n_tie_evals = (int64_t)ties;
     }
     if (best_response_out) memcpy(best_response_out, br.data(), br.size() * sizeof(int32_t));
+    return BSSE_OK;
+}
+
+// --------------------------------------------------------------------------------- top-k
+namespace {
+
+struct DevBuf {                      // device scratch of one call, released on every exit path
+    void *p = nullptr;
+    ~DevBuf() { (void)hipFree(p); }
+    template <typename T> T *as() const { return reinterpret_cast<T *>(p); }
+};
+
+}  // namespace
+
+extern "C" bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev, int64_t count, int k,
+                                       double *values_out, int64_t *indices_out,
+                                       int32_t *best_response_out, int *found_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!values_out || !indices_out || !found_out) return fail(BSSE_EINVAL, "NULL argument");
+    if (k < 1 || k > 256) return fail(BSSE_EINVAL, "k = %d outside 1..256", k);
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    if (count == 0) { *found_out = 0; return BSSE_OK; }
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    const int m = g->m, K = g->K;
+
+    const long long chunk = count < (1LL << 26) ? count : (1LL << 26);
+    const long long nchunks = (count + chunk - 1) / chunk;
+    const long long rec0 = topk_level_blocks(chunk) * k;          // records after the first level
+    DevBuf V, av, ai, bv, bi, wv, wi, rows, br;
+    HIP_TRY(hipMalloc(&V.p, (size_t)chunk * sizeof(float)));
+    HIP_TRY(hipMalloc(&av.p, (size_t)rec0 * sizeof(float)));
+    HIP_TRY(hipMalloc(&ai.p, (size_t)rec0 * sizeof(long long)));
+    HIP_TRY(hipMalloc(&bv.p, (size_t)rec0 * sizeof(float)));
+    HIP_TRY(hipMalloc(&bi.p, (size_t)rec0 * sizeof(long long)));
+    HIP_TRY(hipMalloc(&wv.p, (size_t)(nchunks + 1) * k * sizeof(float)));
+    HIP_TRY(hipMalloc(&wi.p, (size_t)(nchunks + 1) * k * sizeof(long long)));
+    HIP_TRY(hipMalloc(&rows.p, (size_t)k * m * sizeof(float)));
+    HIP_TRY(hipMalloc(&br.p, (size_t)k * K * sizeof(int32_t)));
+
+    // levels from `n` (value, index) records in (sv, si) down to k records, written to (dv, di)
+    auto reduce_to = [&](const float *sv, const long long *si, long long n, long long index_base,
+                         float *dv, long long *di) -> bsse_status {
+        float *pv[2] = { av.as<float>(), bv.as<float>() };
+        long long *pi[2] = { ai.as<long long>(), bi.as<long long>() };
+        int cur = 0;
+        for (;;) {
+            const long long nb = topk_level_blocks(n);
+            float *ov = nb == 1 ? dv : pv[cur];
+            long long *oi = nb == 1 ? di : pi[cur];
+            HIP_TRY(launch_topk_level(sv, si, n, index_base, k, ov, oi, g->stream));
+            if (nb == 1) return BSSE_OK;
+            sv = ov; si = oi; n = nb * k; cur ^= 1;
+        }
+    };
+    for (long long c = 0; c < nchunks; ++c) {
+        const long long base = c * chunk, n = count - base < chunk ? count - base : chunk;
+        SweepArgs a{};
+        a.X = candidates_dev + base * m; a.count = n; a.index_base = 0; a.V_out = V.as<float>();
+        HIP_TRY(launch_sweep(g, a, true));
+        if ((st = reduce_to(V.as<float>(), nullptr, n, base, wv.as<float>() + c * k,
+                            wi.as<long long>() + c * k)) != BSSE_OK) return st;
+    }
+    float *fv = wv.as<float>();
+    long long *fi = wi.as<long long>();
+    if (nchunks > 1) {
+        fv += nchunks * k; fi += nchunks * k;
+        if ((st = reduce_to(wv.as<float>(), wi.as<long long>(), nchunks * k, 0, fv, fi)) != BSSE_OK) return st;
+    }
+    // best responses of the survivors: their rows, evaluated once more with per-candidate outputs
+    HIP_TRY(launch_gather_indexed_rows(candidates_dev, fi, k, m, rows.as<float>(), g->stream));
+    {
+        SweepArgs a{};
+        a.X = rows.as<float>(); a.count = k; a.index_base = 0; a.br_out = br.as<int32_t>();
+        HIP_TRY(launch_sweep(g, a, true));
+    }
+    std::vector<float> hv((size_t)k);
+    std::vector<long long> hi((size_t)k);
+    std::vector<int32_t> hb(best_response_out ? (size_t)k * K : 0);
+    HIP_TRY(hipMemcpyAsync(hv.data(), fv, (size_t)k * sizeof(float), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(hi.data(), fi, (size_t)k * sizeof(long long), hipMemcpyDeviceToHost, g->stream));
+    if (best_response_out)
+        HIP_TRY(hipMemcpyAsync(hb.data(), br.p, hb.size() * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    int found = 0;
+    while (found < k && hi[found] != LLONG_MAX) ++found;
+    for (int r = 0; r < found; ++r) { values_out[r] = (double)hv[r]; indices_out[r] = (int64_t)hi[r]; }
+    if (best_response_out) memcpy(best_response_out, hb.data(), (size_t)found * K * sizeof(int32_t));
+    *found_out = found;
     return BSSE_OK;
 }
 

@@ -115,15 +115,27 @@ hipError_t launch_prior_batch(const float *L, long long count, long long index_b
 hipError_t launch_gather_rows(const float *X, const PriorBest *run, int P, int m, float *rows,
                               hipStream_t s);
 
+// Top-k reduction (see topk.hip): one level turns `count` (value, index) elements (idx null: the
+// index of element e is index_base + e) into k records per workgroup, best first; an index of
+// LLONG_MAX marks an empty record.  topk_level_blocks(count) workgroups.
+long long topk_level_blocks(long long count);
+hipError_t launch_topk_level(const float *vals, const long long *idx, long long count,
+                             long long index_base, int k, float *out_v, long long *out_i,
+                             hipStream_t s);
+hipError_t launch_gather_indexed_rows(const float *X, const long long *idx, int rows, int m,
+                                      float *out, hipStream_t s);
+
 // Host code: the linear program of one pure follower profile (see profile_lp.hip).  Returns 0 with
 // x_out[m] (on the simplex) and *value_out, 1 when the profile is a best response nowhere, 2 when
 // the simplex method hit its iteration limit.  May throw std::bad_alloc.
 int solve_profile_lp(int m, int n, int K, const float *A, const float *B, const float *prior,
                      const int32_t *profile, double *x_out, double *value_out);
 
+// centre (device [m], nullable) and radius: the generated set shrunk towards the centre, each
+// component fl(fl(radius * t) + fl(fl(1 - radius) * centre[i])); centre == nullptr: the plain set.
 hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
-                          float *out, hipStream_t s);
-hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m, float *out,
-                            hipStream_t s);
+                          const float *centre, float radius, float *out, hipStream_t s);
+hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m,
+                            const float *centre, float radius, float *out, hipStream_t s);
 
 }  // namespace bsse

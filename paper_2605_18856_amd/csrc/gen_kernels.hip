@@ -5,6 +5,17 @@
 
 namespace bsse {
 
+// Local sets: with a centre c (device, m floats) the generated point t is replaced by
+// fl(fl(radius * t) + fl(omr * c)), omr = fl(1 - radius): the set shrunk by `radius` towards c.
+// Separately rounded products and sum (no contraction), so the definition is three fp32 operations.
+__device__ __forceinline__ float around(float t, const float *centre, int i, float radius, float omr)
+{
+#pragma clang fp contract(off)
+    if (!centre) return t;
+    const float a = radius * t, b = omr * centre[i];
+    return a + b;
+}
+
 // ---------------------------------------------------------------------------------------
 // Lattice.  Points are the compositions k of N into m parts in ascending lexicographic
 // order.  table[q*(N+1) + R] = W(R, q) = C(R+q-1, q-1), the number of compositions of R
@@ -15,7 +26,7 @@ namespace bsse {
 // S(v) <= rank, found by bisection.
 __global__ void __launch_bounds__(256)
 lattice_kernel(const unsigned long long *__restrict__ table, int m, int N, long long count,
-               float *__restrict__ out)
+               const float *__restrict__ centre, float radius, float omr, float *__restrict__ out)
 {
     const float fN = (float)N;
     const long long stride = (long long)gridDim.x * blockDim.x;
@@ -34,20 +45,20 @@ lattice_kernel(const unsigned long long *__restrict__ table, int m, int N, long 
             }
             rr -= top - Wq1[rem - lo];
             rem -= lo;
-            row[i] = (float)lo / fN;       // IEEE division (correctly rounded)
+            row[i] = around((float)lo / fN, centre, i, radius, omr);   // IEEE division (correctly rounded)
         }
-        row[m - 1] = (float)rem / fN;
+        row[m - 1] = around((float)rem / fN, centre, m - 1, radius, omr);
     }
 }
 
 hipError_t launch_lattice(const unsigned long long *table, int m, int N, long long count,
-                          float *out, hipStream_t s)
+                          const float *centre, float radius, float *out, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
     long long blocks = (count + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(lattice_kernel, dim3((unsigned)blocks), dim3(256), 0, s, table, m, N, count,
-                       out);
+                       centre, radius, 1.0f - radius, out);
     return hipGetLastError();
 }
 
@@ -102,7 +113,8 @@ __device__ __forceinline__ float unit_exponential(unsigned w)
 // that a row's threads sit in one wavefront and the row sum is a butterfly over them.
 __global__ void __launch_bounds__(256)
 dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count, int m,
-                      int log2_nb, float *__restrict__ out)
+                      int log2_nb, const float *__restrict__ centre, float radius, float omr,
+                      float *__restrict__ out)
 {
     const int nb = 1 << log2_nb;
     const long long quads = count << log2_nb;
@@ -129,6 +141,10 @@ dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count
             const float e = 1.0f / (float)m;
             v = make_float4(e, e, e, e);
         }
+        if (centre) {
+            v.x = around(v.x, centre, 4 * b, radius, omr);     v.y = around(v.y, centre, 4 * b + 1, radius, omr);
+            v.z = around(v.z, centre, 4 * b + 2, radius, omr); v.w = around(v.w, centre, 4 * b + 3, radius, omr);
+        }
         if (live) reinterpret_cast<float4 *>(out)[q] = v;
     }
 }
@@ -136,7 +152,7 @@ dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count
 // Any m: one thread per row, two passes over the generator (sum, then normalise).
 __global__ void __launch_bounds__(256)
 dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count, int m,
-                     float *__restrict__ out)
+                     const float *__restrict__ centre, float radius, float omr, float *__restrict__ out)
 {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < count; r += stride) {
@@ -157,14 +173,15 @@ dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count,
             const unsigned ww[4] = { w.x, w.y, w.z, w.w };
             for (int e = 0; e < 4; ++e)
                 if (4 * b + e < m)
-                    out[r * m + 4 * b + e] =
-                        sum > 0.0f ? unit_exponential(ww[e]) * inv : 1.0f / (float)m;
+                    out[r * m + 4 * b + e] = around(
+                        sum > 0.0f ? unit_exponential(ww[e]) * inv : 1.0f / (float)m, centre, 4 * b + e,
+                        radius, omr);
         }
     }
 }
 
-hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m, float *out,
-                            hipStream_t s)
+hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int m,
+                            const float *centre, float radius, float *out, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
     const unsigned k0 = (unsigned)(seed & 0xFFFFFFFFull), k1 = (unsigned)(seed >> 32);
@@ -177,12 +194,12 @@ hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int
         long long blocks = (quads + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
         hipLaunchKernelGGL(dirichlet_quad_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
-                           first, count, m, log2_nb, out);
+                           first, count, m, log2_nb, centre, radius, 1.0f - radius, out);
     } else {
         long long blocks = (count + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
         hipLaunchKernelGGL(dirichlet_row_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
-                           first, count, m, out);
+                           first, count, m, centre, radius, 1.0f - radius, out);
     }
     return hipGetLastError();
 }

@@ -1,0 +1,82 @@
+"""Local candidate sets (bsse_lattice_around, bsse_dirichlet_around) against the oracle's
+generators, and a top-k + local re-sweep refinement on a hand-solved game."""
+import numpy as np
+import pytest
+
+from oracle import dirichlet as odir
+from oracle import lattice as olat
+from paper_2605_18856_amd import bsse, workloads
+from tests.test_gpu_parity import _make
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("m,N,radius", [(3, 20, 0.25), (3, 7, 0.1), (4, 9, 0.3), (8, 4, 0.0625),
+                                        (5, 6, 1.0), (5, 6, 0.0), (2, 33, 0.7)])
+def test_lattice_around_bit_exact(m, N, radius):
+    game = workloads.small_game(m, 3, 2, seed=1, kind="normal")
+    rng = np.random.default_rng(m * 100 + N)
+    centre = rng.dirichlet(np.ones(m)).astype(np.float32)
+    with _make(game) as g:
+        cnt = bsse.bsse_lattice_around(g, N, centre, radius)
+        got = bsse.candidates_to_host(g)
+    ref = olat.points_around_f32(m, N, centre, radius)
+    assert cnt == ref.shape[0]
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("m", [3, 8, 32])
+def test_dirichlet_around_against_oracle(m):
+    import torch
+    game = workloads.small_game(m, 3, 2, seed=1, kind="normal")
+    centre = np.random.default_rng(m).dirichlet(np.ones(m)).astype(np.float32)
+    with _make(game) as g:
+        out = torch.empty((500, m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet_around(g, 77, 1000, 500, centre, 0.125, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+    ref = odir.rows_around(77, 1000, 500, m, centre, 0.125)
+    assert np.allclose(got, ref, rtol=2e-6, atol=1e-9)
+    assert np.all(np.abs(got.sum(axis=1) - 1.0) <= 1e-6)
+    assert np.all(np.abs(got - centre[None, :]) <= 0.125 + 1e-6)
+
+
+def test_argument_errors():
+    game = workloads.small_game(3, 3, 2, seed=1, kind="normal")
+    with _make(game) as g:
+        for radius in (-0.1, 1.5, float("nan")):
+            with pytest.raises(bsse.BsseError) as e:
+                bsse.bsse_lattice_around(g, 4, [0.2, 0.3, 0.5], radius)
+            assert e.value.status == bsse.BSSE_EINVAL
+        with pytest.raises(bsse.BsseError) as e:
+            bsse.bsse_lattice_around(g, 4, [0.2, np.inf, 0.5], 0.5)
+        assert e.value.status == bsse.BSSE_ENOTFINITE
+
+
+def test_topk_then_local_resweep_on_the_hand_game():
+    """A = [[2,4],[1,3]], B = [[1,0],[0,1]] (tests/golden/hand_tiebreak_2x2.txt): V = 3 + x0 for
+    x0 <= 1/2 and 1 + x0 above.  A lattice of resolution 5 stops at x0 = 2/5 (V = 3.4).  Re-sweeping
+    a resolution-64 lattice shrunk to radius 1/4 around each of the two best points must find a
+    better commitment below the equilibrium value 3.5, and a second round closes in further."""
+    A = np.array([[[2, 4], [1, 3]]], np.float32)
+    B = np.array([[[1, 0], [0, 1]]], np.float32)
+    with bsse.bsse_create(2, 2, 1, A, B, np.ones(1, np.float32)) as g:
+        bsse.bsse_lattice(g, 5)
+        first = bsse.bsse_sweep(g)
+        assert abs(first.best_value - 3.4) < 1e-6
+        radius, best = 0.25, first.best_value
+        for rnd in range(2):
+            vals, idx, _ = bsse.bsse_sweep_topk(g, 2)
+            X = bsse.candidates_to_host(g)
+            centres = X[idx]
+            round_best = -np.inf
+            for c in centres:
+                bsse.bsse_lattice_around(g, 64, c, radius)
+                out = bsse.bsse_sweep(g)
+                if out.best_value > round_best:
+                    round_best, keep = out.best_value, c.copy()
+            assert best <= round_best <= 3.5 + 1e-6
+            best = round_best
+            bsse.bsse_lattice_around(g, 64, keep, radius)        # the set the next round refines
+            radius *= 0.25
+        assert best > 3.49

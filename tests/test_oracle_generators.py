@@ -91,3 +91,39 @@ def test_dirichlet_marginals_are_beta(m):
     cov = np.cov(X[:, 0], X[:, 1])[0, 1]
     var = (m - 1) / (m * m * (m + 1.0))
     assert cov == pytest.approx(-1.0 / (m * m * (m + 1.0)), abs=6 * var / np.sqrt(20000))
+
+
+def test_lattice_around_exact_rational_cases_and_limits():
+    """The shrunk lattice against exact rational arithmetic where every operation is exact in
+    float32 (dyadic centre, radius and 1/N), and its two limits."""
+    from fractions import Fraction as F
+    m, N = 3, 4
+    centre = [F(1, 2), F(1, 4), F(1, 4)]
+    radius = F(1, 4)
+    got = lattice.points_around_f32(m, N, [float(c) for c in centre], float(radius))
+    comps = lattice.compositions(m, N)
+    assert got.shape == (len(comps), m)
+    for row, k in zip(got, comps):
+        for i in range(m):
+            exact = (1 - radius) * centre[i] + radius * F(int(k[i]), N)
+            assert F(float(row[i])) == exact                    # no rounding happened anywhere
+        assert sum(F(float(v)) for v in row) == 1
+    plain = lattice.points_f32(m, N)
+    assert np.array_equal(lattice.points_around_f32(m, N, [0.2, 0.3, 0.5], 1.0), plain)
+    rep = lattice.points_around_f32(m, N, [0.2, 0.3, 0.5], 0.0)
+    assert np.array_equal(rep, np.tile(np.float32([0.2, 0.3, 0.5]), (len(comps), 1)))
+    # generic case: inside the simplex, within radius of the centre (L-infinity), order kept
+    c = np.float32([0.1, 0.6, 0.3])
+    pts = lattice.points_around_f32(m, 10, c, 0.125)
+    assert np.all(pts >= 0) and np.all(np.abs(pts.sum(axis=1) - 1) < 1e-6)
+    assert np.all(np.abs(pts - c[None, :]) <= 0.125 + 1e-6)
+    assert np.all(np.diff(pts[:, 0]) >= 0)                      # lexicographic order survives the map
+
+
+def test_dirichlet_around_is_the_affine_image():
+    c = np.float32([0.5, 0.25, 0.125, 0.125])
+    base = dirichlet.rows(11, 5, 40, 4)
+    loc = dirichlet.rows_around(11, 5, 40, 4, c, 0.25)
+    assert np.allclose(loc, 0.75 * c[None, :].astype(np.float64) + 0.25 * base, rtol=0, atol=1e-15)
+    assert np.allclose(loc.sum(axis=1), 1.0, atol=1e-12)
+    assert np.array_equal(dirichlet.rows_around(11, 5, 40, 4, c, 1.0), base)
