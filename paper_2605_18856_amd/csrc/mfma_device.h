@@ -187,6 +187,40 @@ __device__ __forceinline__ void bitmap16x2(const float *ua, float ga, unsigned &
         : "vcc");
 #undef BSSE_BM4X2
 }
+// Sixteen values as two interleaved streams of eight (u[0..7] and u[8..15]) against one maximum:
+// returns the 16-bit map with bit 15 - r set iff u[r] == gmax.
+__device__ __forceinline__ unsigned bitmap16_split(const float *u, float gmax)
+{
+    unsigned ba = 0u, bb = 0u;
+    unsigned long long m0, m1, m2, m3, m4, m5, m6;
+#define BSSE_BM4S(a, b, c, d, e, f, g, h)                                       \
+        "v_cmp_eq_f32 %[m0], %[u" #a "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m1], %[u" #e "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m2], %[u" #b "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m3], %[u" #f "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m4], %[u" #c "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m5], %[u" #g "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m6], %[u" #d "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 vcc, %[u" #h "], %[g]\n\t"                                \
+        "v_addc_co_u32_e64 %[ba], %[m0], %[ba], %[ba], %[m0]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m1], %[bb], %[bb], %[m1]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m2], %[ba], %[ba], %[m2]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m3], %[bb], %[bb], %[m3]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m4], %[ba], %[ba], %[m4]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m5], %[bb], %[bb], %[m5]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m6], %[ba], %[ba], %[m6]\n\t"               \
+        "v_addc_co_u32_e32 %[bb], vcc, %[bb], %[bb], vcc\n\t"
+    asm(BSSE_BM4S(0, 1, 2, 3, 8, 9, 10, 11) BSSE_BM4S(4, 5, 6, 7, 12, 13, 14, 15)
+        : [ba] "+v"(ba), [bb] "+v"(bb), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+          [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6)
+        : [u0] "v"(u[0]), [u1] "v"(u[1]), [u2] "v"(u[2]), [u3] "v"(u[3]), [u4] "v"(u[4]),
+          [u5] "v"(u[5]), [u6] "v"(u[6]), [u7] "v"(u[7]), [u8] "v"(u[8]), [u9] "v"(u[9]),
+          [u10] "v"(u[10]), [u11] "v"(u[11]), [u12] "v"(u[12]), [u13] "v"(u[13]), [u14] "v"(u[14]),
+          [u15] "v"(u[15]), [g] "v"(gmax)
+        : "vcc");
+#undef BSSE_BM4S
+    return (ba << 8) | bb;
+}
 __device__ __forceinline__ void vmax_chain16x2(float &pa, const float *ua, float &pb, const float *ub)
 {
 #define BSSE_MX(a, b)                                                           \

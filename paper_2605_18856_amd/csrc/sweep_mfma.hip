@@ -193,7 +193,7 @@ typedef void __attribute__((address_space(3))) *lds_ptr;
 // sequence does not depend on NT, OCC or SLICED, so every instantiation of a packing gives the
 // same bits for the same row.
 template <typename T, int MP, int N, int NT, int WAVES, int STAGE_TILES, int OCC, bool AT_LDS, int TERMS,
-          bool SLICED>
+          bool SLICED, int PF>
 __global__ void __launch_bounds__(WAVES * 64, OCC)
 sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 {
@@ -358,14 +358,50 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[ct][tt][r] = 0.0f;
     };
-    // MFMAs of row tile tt of the group (fragments in LDS) against all NT candidate tiles
-    auto mfma_tile = [&](const frag *tf, int tt) __attribute__((always_inline)) {
+    // MFMAs of NTILES consecutive row tiles (fragments in LDS at `base`; tt0 = index of the first
+    // one within the group) against all NT candidate tiles.  The fragment reads are software-
+    // pipelined in chunks of PF k-steps where that was measured to pay (the wide bf16 game): the
+    // reads of chunk q+1 are issued before the MFMAs of chunk q, so the LDS latency runs under the
+    // matrix pipe instead of in front of it.
+    auto mfma_run = [&](const frag *base, auto ntiles_c, auto tt0_c) __attribute__((always_inline)) {
+        constexpr int NTILES = decltype(ntiles_c)::value, TT0 = decltype(tt0_c)::value;
+        if constexpr (PF == 0) {               // reads where they are used; the compiler schedules
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const frag af = tf[s * 64 + lane];
+            for (int tt = 0; tt < NTILES; ++tt)
 #pragma unroll
-            for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(af, x[ct], s, acc[ct][tt]);
+                for (int ks = 0; ks < KS; ++ks) {
+                    const frag af = base[(size_t)tt * TILE_FRAGS + (size_t)ks * 64 + lane];
+#pragma unroll
+                    for (int ct = 0; ct < NT; ++ct) acc[ct][TT0 + tt] = P::mfma(af, x[ct], ks, acc[ct][TT0 + tt]);
+                }
+            return;
         }
+        static_assert(PF == 0 || KS % (PF ? PF : 1) == 0, "fragment chunk must divide the k-steps of a tile");
+        constexpr int C = PF ? PF : 1;
+        constexpr int NCH = NTILES * KS / C;
+        frag fb[2][C];
+        const frag *lane_base = base + lane;
+#pragma unroll
+        for (int e = 0; e < C; ++e) fb[0][e] = lane_base[(size_t)e * 64];
+        static_for<0, NCH, 1>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            if constexpr (q + 1 < NCH) {
+#pragma unroll
+                for (int e = 0; e < C; ++e) {
+                    constexpr int f0 = (q + 1) * C;
+                    const int f = f0 + e;                                    // flat (tile, k-step)
+                    fb[(q + 1) & 1][e] = lane_base[(size_t)(f / KS) * TILE_FRAGS + (size_t)(f % KS) * 64];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, C, 1>([&](auto ec) {
+                constexpr int f = q * C + decltype(ec)::value;
+                constexpr int tt = TT0 + f / KS, ks = f % KS;
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(fb[q & 1][decltype(ec)::value], x[ct], ks, acc[ct][tt]);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
     // per-type epilogue of a finished group; at_lds = LDS rows of the group's first type
     auto epilogue = [&](int group, const lds_byte *at_lds) __attribute__((always_inline)) {
@@ -381,7 +417,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             for (int ct = 0; ct < NT; ++ct) {
                 // lane maximum over this type's registers
                 float pm = -INFINITY;
-                unsigned total = 0u;
+                unsigned total = 0u, tile_tie = 0u;       // tile_tie: wave-uniform column mask
                 float gm;
                 if constexpr (N >= 32) {
                     // whole row tiles belong to the type: one asm block per 16 registers for the
@@ -397,39 +433,53 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                         match8(u[0], gm, creg, total);
                         match8(u[0] + 8, gm, creg + 8, total);
                     } else {
-                        // tile tt goes with tile tt + TPG/2: two independent instruction streams
+                        // Lane maximum per row tile (tile tt goes with tile tt + TPG/2: two
+                        // independent instruction streams), then over the tiles.
                         constexpr int HT = TPG / 2;
-                        float pb = -INFINITY;
+                        float pmt[TPG];
+#pragma unroll
+                        for (int k = 0; k < TPG; ++k) pmt[k] = -INFINITY;
                         static_for<0, HT, 1>([&](auto ttc) {
                             constexpr int tt = decltype(ttc)::value;
-                            vmax_chain16x2(pm, u[tt], pb, u[tt + HT]);
+                            vmax_chain16x2(pmt[tt], u[tt], pmt[tt + HT], u[tt + HT]);
                         });
-                        gm = pair_max(vmax2(pm, pb));
-                        // compare pass as a bitmap: one bit per value, first value highest; 32
-                        // values (two row tiles) per word
-                        constexpr int NW = HT;
-                        unsigned w[NW];
-                        if constexpr (TPG == 2) {
-                            unsigned wa = 0u, wb = 0u;
-                            bitmap16x2(u[0], gm, wa, u[1], gm, wb);
-                            w[0] = (wa << 16) | wb;
-                        } else {
+                        pm = pmt[0];
 #pragma unroll
-                            for (int k = 0; k < NW; ++k) w[k] = 0u;
-                            static_for<0, HT, 1>([&](auto ttc) {
-                                constexpr int tt = decltype(ttc)::value;
-                                bitmap16x2(u[tt], gm, w[tt / 2], u[tt + HT], gm, w[(tt + HT) / 2]);
-                            });
-                        }
-                        unsigned cnt = 0u, pos = 0xFFFFFFFFu;  // maximisers of the lane; first one
+                        for (int k = 1; k + 1 < TPG; k += 2) pm = vmax3(pm, pmt[k], pmt[k + 1]);
+                        pm = vmax2(pm, pmt[TPG - 1]);
+                        gm = pair_max(pm);
+                        // Only a tile whose maximum is the pair's maximum can hold a maximiser.
+                        // Two such tiles in one lane are a tie (exact routine); otherwise the
+                        // tile's sixteen registers are selected (a tournament of conditional
+                        // moves, (TPG-1)*16 of them) and the compare pass runs on those alone:
+                        // (TPG-1)*16 + 32 instructions instead of TPG*32.
+                        bool e[TPG];
+                        unsigned tile[TPG];
+                        unsigned long long seen = 0ull, dup = 0ull;
 #pragma unroll
-                        for (int k = 0; k < NW; ++k) {
-                            cnt += (unsigned)__builtin_popcount(w[k]);
-                            const unsigned f = ffbh(w[k]) | (32u * k);   // stays 0xFFFFFFFF for no bit
-                            pos = f < pos ? f : pos;
+                        for (int k = 0; k < TPG; ++k) {
+                            e[k] = pmt[k] == gm;
+                            tile[k] = (unsigned)k;
+                            const unsigned long long mk = __builtin_amdgcn_ballot_w64(e[k]);
+                            dup |= seen & mk;
+                            seen |= mk;
                         }
-                        // position = 16 * tile + register  ->  action 32 * tile + row(register) + 4h
-                        const unsigned act = ((pos & 0xFCu) << 1) | (pos & 3u) | (4u * h);
+                        tile_tie |= (unsigned)(dup | (dup >> 32));
+#pragma unroll
+                        for (int nn = TPG; nn > 1; nn >>= 1)
+#pragma unroll
+                            for (int j = 0; j < nn / 2; ++j) {
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) u[j][r] = e[2 * j + 1] ? u[2 * j + 1][r] : u[2 * j][r];
+                                tile[j] = e[2 * j + 1] ? tile[2 * j + 1] : tile[2 * j];
+                                e[j] = e[2 * j] || e[2 * j + 1];
+                            }
+                        // compare pass as a bitmap: bit 15 - r set iff register r is a maximiser
+                        const unsigned w = bitmap16_split(u[0], gm);
+                        const unsigned cnt = (unsigned)__builtin_popcount(w);
+                        const unsigned r = ffbh(w) - 16u;
+                        // action = 32 * tile + row(register) + 4h
+                        const unsigned act = (tile[0] << 5) | ((r & 0xCu) << 1) | (r & 3u) | (4u * h);
                         total = cnt ? (cnt << 16) | act : 0u;
                     }
                 } else {
@@ -454,7 +504,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 const unsigned pair = pair_add_u32(total);
                 gmax[ct] = gm;
                 jstar[ct] = (int)(pair & 0xFFFFu);
-                const unsigned multi = (unsigned)__builtin_amdgcn_ballot_w64((pair >> 16) != 1u);
+                const unsigned multi = (unsigned)__builtin_amdgcn_ballot_w64((pair >> 16) != 1u) | tile_tie;
                 clean[ct] = (multi & valid32[ct]) == 0u && valid32[ct] == 0xFFFFFFFFu;   // wave-uniform
             }
 #pragma unroll
@@ -498,8 +548,8 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll 1
             for (int gi = 0; gi < ng; ++gi) {
                 zero_acc();
-#pragma unroll
-                for (int tt = 0; tt < TPG; ++tt) mfma_tile(tiles + (size_t)(gi * TPG + tt) * TILE_FRAGS, tt);
+                mfma_run(tiles + (size_t)(gi * TPG) * TILE_FRAGS, std::integral_constant<int, TPG>{},
+                         std::integral_constant<int, 0>{});
                 epilogue(g0 + gi, (const lds_byte *)buf + (unsigned)(STAGE_TILES * G.tile_bytes + gi * TYPES * N * G.ats * sizeof(T)));
             }
             stage_sync();
@@ -515,10 +565,8 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 constexpr int ss = decltype(ssc)::value;
                 if (st + 1 < stage_end) prefetch(st + 1);
                 const frag *tiles = reinterpret_cast<const frag *>(smem + (st & 1) * G.rec_bytes);
-                static_for<0, STAGE_TILES, 1>([&](auto t2c) {
-                    constexpr int t2 = decltype(t2c)::value;
-                    mfma_tile(tiles + (size_t)t2 * TILE_FRAGS, ss * STAGE_TILES + t2);
-                });
+                mfma_run(tiles, std::integral_constant<int, STAGE_TILES>{},
+                         std::integral_constant<int, ss * STAGE_TILES>{});
                 if constexpr (ss == SPG - 1) epilogue(gr, nullptr);
                 stage_sync();
                 ++st;
@@ -591,29 +639,30 @@ struct Variant {
     const char *name;
 };
 
-#define BSSE_VARIANT(T, MODE, TERMSv, MPB, Nv, NTv, Wv, STv, OCCv, ATL, NAME)                        \
+#define BSSE_VARIANT(T, MODE, TERMSv, MPB, Nv, NTv, Wv, STv, OCCv, ATL, PFv, NAME)                   \
     { MODE, TERMSv, MPB, Nv, NTv, Wv, STv, ATL,                                                      \
-      sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv, false>,                \
-      sweep_mfma_kernel<T, MPB * TERMSv, Nv, 1, Wv, STv, 1, ATL, TERMSv, true>,                      \
+      sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv, false, PFv>,           \
+      sweep_mfma_kernel<T, MPB * TERMSv, Nv, 1, Wv, STv, 1, ATL, TERMSv, true, PFv>,                 \
       make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME }
 
 const Variant kVariants[] = {
-    // fp32 MFMA
-    BSSE_VARIANT(float, 0, 1, 8, 8, 4, 4, 1, 2, true, "mfma_f32"),
-    BSSE_VARIANT(float, 0, 1, 16, 16, 4, 4, 2, 2, true, "mfma_f32"),
-    BSSE_VARIANT(float, 0, 1, 32, 32, 4, 4, 4, 2, true, "mfma_f32"),
-    BSSE_VARIANT(float, 0, 1, 32, 64, 2, 4, 4, 2, true, "mfma_f32"),
-    BSSE_VARIANT(float, 0, 1, 128, 256, 1, 4, 2, 2, false, "mfma_f32"),
+    // fp32 MFMA (the last number before the name: k-steps per fragment read-ahead chunk, 0 = the
+    // fragment reads are left where they are used)
+    BSSE_VARIANT(float, 0, 1, 8, 8, 4, 4, 1, 2, true, 0, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 16, 16, 4, 4, 2, 2, true, 0, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 32, 32, 4, 4, 4, 2, true, 0, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 32, 64, 2, 4, 4, 2, true, 0, "mfma_f32"),
+    BSSE_VARIANT(float, 0, 1, 128, 256, 1, 4, 2, 2, false, 0, "mfma_f32"),
     // bf16 MFMA, operands rounded to bf16
-    BSSE_VARIANT(__bf16, 1, 1, 16, 32, 4, 4, 2, 2, true, "mfma_bf16"),
-    BSSE_VARIANT(__bf16, 1, 1, 32, 16, 4, 4, 2, 2, false, "mfma_bf16"),
-    BSSE_VARIANT(__bf16, 1, 1, 64, 128, 2, 4, 4, 2, true, "mfma_bf16"),
+    BSSE_VARIANT(__bf16, 1, 1, 16, 32, 4, 4, 2, 2, true, 0, "mfma_bf16"),
+    BSSE_VARIANT(__bf16, 1, 1, 32, 16, 4, 4, 2, 2, false, 0, "mfma_bf16"),
+    BSSE_VARIANT(__bf16, 1, 1, 64, 128, 2, 4, 4, 2, true, 4, "mfma_bf16"),
     // bf16 MFMA on fp32 operands split into bf16 parts
-    BSSE_VARIANT(__bf16, 2, 6, 16, 16, 2, 4, 2, 2, true, "mfma_split6"),
-    BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 8, 1, 3, true, "mfma_split6"),
-    BSSE_VARIANT(__bf16, 2, 3, 32, 32, 4, 4, 4, 2, true, "mfma_split3"),
-    BSSE_VARIANT(__bf16, 2, 6, 32, 64, 2, 4, 2, 2, true, "mfma_split6"),
-    BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 1, 2, false, "mfma_split3"),
+    BSSE_VARIANT(__bf16, 2, 6, 16, 16, 2, 4, 2, 2, true, 0, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 8, 1, 3, true, 0, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 3, 32, 32, 4, 4, 4, 2, true, 0, "mfma_split3"),
+    BSSE_VARIANT(__bf16, 2, 6, 32, 64, 2, 4, 2, 2, true, 0, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 1, 2, false, 0, "mfma_split3"),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 constexpr int kSmallVariant = 1000;          // the small-game kernel (sweep_small.hip)
