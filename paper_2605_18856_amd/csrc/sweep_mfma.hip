@@ -403,8 +403,43 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             __builtin_amdgcn_sched_barrier(0);
         });
     };
+    // second half of a type's epilogue: leader payoff at the best response (fast path: one row
+    // gather and a dot product; otherwise the exact routine), value accumulation, outputs
+    auto leader_part = [&](int group, int ti, int t, float pt, const lds_byte *at_lds, const float *gmax,
+                           const int *jstar, const bool *clean) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            float l;
+            int js = jstar[ct];
+            if (clean[ct]) {
+                float part;
+                if constexpr (AT_LDS)
+                    part = P::half_dot(x[ct], at_lds + (unsigned)(((ti * N + js) * G.ats + h * HALF) * sizeof(T)));
+                else
+                    part = P::half_dot(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
+                l = pair_sum(part);
+            } else {
+                exact_type(ct, group, ti, t, gmax[ct], l, js);
+            }
+            V[ct] = fmaf(pt, l, V[ct]);
+            if (a.br_out) {
+                const long long c = wave_base + ct * 32 + col;
+                if (h == 0 && c < a.count) a.br_out[c * K + t] = js;
+            }
+            if constexpr (SLICED) {
+                const long long c = wave_base + ct * 32 + col;
+                if (h == 0 && c < a.count) a.l_out[c * K + t] = l;
+            }
+        }
+    };
     // per-type epilogue of a finished group; at_lds = LDS rows of the group's first type
     auto epilogue = [&](int group, const lds_byte *at_lds) __attribute__((always_inline)) {
+        // The asm blocks below read the accumulators, and the compiler's hazard handling does not
+        // look into inline asm: the wait states a vector read of a fresh MFMA result needs (passes
+        // + 3: 11 for the 8-pass bf16 MFMA, 19 for the 16-pass fp32 one) are put here explicitly.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15");
+        if constexpr (std::is_same<T, float>::value) asm volatile("s_nop 3");
         static_for<0, TYPES, 1>([&](auto tic) {
             constexpr int ti = decltype(tic)::value;
             const int t = group * TYPES + ti;
@@ -507,30 +542,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 const unsigned multi = (unsigned)__builtin_amdgcn_ballot_w64((pair >> 16) != 1u) | tile_tie;
                 clean[ct] = (multi & valid32[ct]) == 0u && valid32[ct] == 0xFFFFFFFFu;   // wave-uniform
             }
-#pragma unroll
-            for (int ct = 0; ct < NT; ++ct) {
-                float l;
-                int js = jstar[ct];
-                if (clean[ct]) {
-                    float part;
-                    if constexpr (AT_LDS)
-                        part = P::half_dot(x[ct], at_lds + (unsigned)(((ti * N + js) * G.ats + h * HALF) * sizeof(T)));
-                    else
-                        part = P::half_dot(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
-                    l = pair_sum(part);
-                } else {
-                    exact_type(ct, group, ti, t, gmax[ct], l, js);
-                }
-                V[ct] = fmaf(pt, l, V[ct]);
-                if (a.br_out) {
-                    const long long c = wave_base + ct * 32 + col;
-                    if (h == 0 && c < a.count) a.br_out[c * K + t] = js;
-                }
-                if constexpr (SLICED) {
-                    const long long c = wave_base + ct * 32 + col;
-                    if (h == 0 && c < a.count) a.l_out[c * K + t] = l;
-                }
-            }
+            leader_part(group, ti, t, pt, at_lds, gmax, jstar, clean);
         });
     };
 
