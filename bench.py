@@ -134,14 +134,18 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
         c0 = time.perf_counter()
         osweep.sweep(game.A, game.B, game.prior, Xp, per_candidate=False, nthreads=cores)
         per_row = max((time.perf_counter() - c0) / probe, 1e-9)
-        sample = int(min(count, max(probe, 15.0 / per_row)))
-        passes = max(1, int(15.0 / (per_row * sample))) if sample == count else 1
-        passes = min(passes, 2000)
+        sample = int(min(count, max(probe, 12.0 / per_row)))
         Xh = rows(sample)
+        # passes over the sample until about 12 s of oracle time have been spent (the probe
+        # over-estimates the cost per row of a small game, so the count is not fixed in advance)
+        passes = 0
         c0 = time.perf_counter()
-        for _ in range(passes):
+        while True:
             ref = osweep.sweep(game.A, game.B, game.prior, Xh, per_candidate=False, nthreads=cores)
-        c1 = time.perf_counter()
+            passes += 1
+            c1 = time.perf_counter()
+            if c1 - c0 >= 12.0 or passes >= 20000 or sample < count:
+                break
         cpu = {"value": passes * sample * game.K / (c1 - c0), "unit": "candidate-type evals/s",
                "cores": ref.threads, "kind": "oracle",
                "sample": f"{passes} pass(es) over the first {sample} candidates of the step's "
