@@ -204,6 +204,22 @@ bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev, int64_t c
                             double *values_out, int64_t *indices_out, int32_t *best_response_out,
                             int *found_out);
 
+/* Refinement: top-k and local re-sweeps in rounds, starting from the handle-owned generated set
+ * (BSSE_ESTATE if none).  The k best candidates of that set are the first centres; in every
+ * round a local set is generated around each centre -- the lattice of resolution lattice_N
+ * (bsse_lattice_around) when lattice_N > 0, else cloud_count Dirichlet rows
+ * (bsse_dirichlet_around with seed + round * 1000003 + centre number) -- and swept with
+ * bsse_sweep_topk; the k best distinct points among the centres and everything found become the
+ * next centres, and the radius is multiplied by shrink.  1 <= k <= 256, 1 <= rounds <= 64,
+ * radius and shrink in (0, 1]; exactly one of lattice_N, cloud_count positive.  x_out = host [m]
+ * the best point found, res->best_value its V as the kernels compute it (never below the best of
+ * the starting set), res->best_index = -1, res->n_evals the evaluations spent,
+ * best_response_out = host [K] or NULL.  The handle-owned set is overwritten.  Waits for the
+ * stream. */
+bsse_status bsse_refine(bsse_game *g, int k, int rounds, int lattice_N, int64_t cloud_count,
+                        uint64_t seed, float radius, float shrink, float *x_out, bsse_result *res,
+                        int32_t *best_response_out);
+
 /* LP polish.  The sweep only sees its candidates; the linear program of the winner's best-response
  * profile lands on the exact vertex of that profile's region (one program of the multiple-LPs
  * characterisation of the strong Stackelberg equilibrium):

@@ -25,7 +25,7 @@ EXPORTS = [
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
-    "bsse_dirichlet_around",
+    "bsse_dirichlet_around", "bsse_refine",
 ]
 
 
@@ -83,6 +83,8 @@ def lib():
     L.bsse_polish.argtypes = [vp, vp, vp, P(bsse_result), vp, P(ctypes.c_double)]
     L.bsse_sweep_topk.argtypes = [vp, vp, i64, i32, vp, vp, vp, P(i32)]
     L.bsse_lattice_around.argtypes = [vp, i32, vp, ctypes.c_float, P(i64)]
+    L.bsse_refine.argtypes = [vp, i32, i32, i32, i64, u64, ctypes.c_float, ctypes.c_float, vp,
+                              P(bsse_result), vp]
     L.bsse_dirichlet_around.argtypes = [vp, u64, i64, i64, vp, ctypes.c_float, vp]
     L.bsse_path_name.argtypes = [vp]
     L.bsse_path_name.restype = ctypes.c_char_p
@@ -326,6 +328,19 @@ def bsse_sweep_topk(g: Game, k: int, candidates=None, count: Optional[int] = Non
                                  v.ctypes.data, idx.ctypes.data, br.ctypes.data, ctypes.byref(found)))
     f = found.value
     return v[:f].copy(), idx[:f].copy(), br[:f].copy()
+
+
+def bsse_refine(g: Game, k: int, rounds: int, lattice_N: int = 0, cloud_count: int = 0, seed: int = 0,
+                radius: float = 0.25, shrink: float = 0.25):
+    """(x float32 [m], value, best responses int32 [K], evaluations spent) after `rounds` rounds of
+    top-k + local re-sweep starting from the handle-owned generated set."""
+    x = np.zeros(g.m, dtype=np.float32)
+    br = np.full(g.K, -1, dtype=np.int32)
+    res = bsse_result()
+    _check(lib().bsse_refine(g.handle, int(k), int(rounds), int(lattice_N), int(cloud_count),
+                             ctypes.c_uint64(seed), float(radius), float(shrink), x.ctypes.data,
+                             ctypes.byref(res), br.ctypes.data))
+    return x, res.best_value, br, res.n_evals
 
 
 def bsse_profile_lp(A, B, prior, profile):

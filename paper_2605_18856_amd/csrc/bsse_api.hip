@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <algorithm>
 #include <vector>
 
 using namespace bsse;
@@ -899,6 +900,94 @@ extern "C" bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev
     for (int r = 0; r < found; ++r) { values_out[r] = (double)hv[r]; indices_out[r] = (int64_t)hi[r]; }
     if (best_response_out) memcpy(best_response_out, hb.data(), (size_t)found * K * sizeof(int32_t));
     *found_out = found;
+    return BSSE_OK;
+}
+
+// ------------------------------------------------------------------------------- refinement
+extern "C" bsse_status bsse_refine(bsse_game *g, int k, int rounds, int lattice_N, int64_t cloud_count,
+                                   uint64_t seed, float radius, float shrink, float *x_out,
+                                   bsse_result *res, int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!x_out || !res) return fail(BSSE_EINVAL, "NULL argument");
+    if (k < 1 || k > 256) return fail(BSSE_EINVAL, "k = %d outside 1..256", k);
+    if (rounds < 1 || rounds > 64) return fail(BSSE_EINVAL, "rounds = %d outside 1..64", rounds);
+    if ((lattice_N > 0) == (cloud_count > 0))
+        return fail(BSSE_EINVAL, "give either lattice_N > 0 or cloud_count > 0");
+    if (!(radius > 0.0f && radius <= 1.0f) || !(shrink > 0.0f && shrink <= 1.0f))
+        return fail(BSSE_EINVAL, "radius and shrink must lie in (0, 1]");
+    if (g->gen_count <= 0) return fail(BSSE_ESTATE, "no candidate set has been generated on this handle");
+    const int m = g->m, K = g->K;
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+
+    // survivors: value, row, best responses; kept sorted by (value desc, order of discovery)
+    struct Survivor { double v; std::vector<float> x; std::vector<int32_t> br; };
+    std::vector<Survivor> pool;
+    std::vector<double> vals((size_t)k);
+    std::vector<int64_t> idx((size_t)k);
+    std::vector<int32_t> brs((size_t)k * K);
+    long long evals = 0;
+    // the k best of the handle's current set, with their rows, into `into`
+    auto harvest = [&](std::vector<Survivor> &into) -> bsse_status {
+        int found = 0;
+        bsse_status st = bsse_sweep_topk(g, nullptr, 0, k, vals.data(), idx.data(), brs.data(), &found);
+        if (st != BSSE_OK) return st;
+        evals += (long long)g->gen_count * K;
+        for (int r = 0; r < found; ++r) {
+            Survivor sv;
+            sv.v = vals[r];
+            sv.x.resize((size_t)m);
+            sv.br.assign(brs.begin() + (size_t)r * K, brs.begin() + (size_t)(r + 1) * K);
+            HIP_TRY(hipMemcpy(sv.x.data(), g->gen + (size_t)idx[r] * m, (size_t)m * sizeof(float),
+                              hipMemcpyDeviceToHost));
+            into.push_back(std::move(sv));
+        }
+        return BSSE_OK;
+    };
+    auto keep_best = [&](std::vector<Survivor> &v) {
+        std::stable_sort(v.begin(), v.end(), [](const Survivor &a, const Survivor &b) { return a.v > b.v; });
+        // the same point may be found from two centres: keep one
+        std::vector<Survivor> out;
+        for (auto &sv : v) {
+            bool dupl = false;
+            for (auto &o : out) if (o.x == sv.x) { dupl = true; break; }
+            if (!dupl) out.push_back(std::move(sv));
+            if ((int)out.size() == k) break;
+        }
+        v.swap(out);
+    };
+    bsse_status st;
+    try {
+        if ((st = harvest(pool)) != BSSE_OK) return st;
+        keep_best(pool);
+        float rad = radius;
+        for (int round = 0; round < rounds; ++round) {
+            std::vector<Survivor> next = pool;             // a centre survives unless it is beaten
+            for (size_t c = 0; c < pool.size(); ++c) {
+                if (lattice_N > 0) {
+                    int64_t cnt = 0;
+                    st = bsse_lattice_around(g, lattice_N, pool[c].x.data(), rad, &cnt);
+                } else {
+                    st = bsse_dirichlet_around(g, seed + (uint64_t)round * 1000003ull + c, 0, cloud_count,
+                                               pool[c].x.data(), rad, nullptr);
+                }
+                if (st != BSSE_OK) return st;
+                if ((st = harvest(next)) != BSSE_OK) return st;
+            }
+            keep_best(next);
+            pool.swap(next);
+            rad *= shrink;
+        }
+    } catch (...) { return fail(BSSE_ENOMEM, "host allocation failed"); }
+    if (pool.empty()) return fail(BSSE_ESTATE, "the candidate set is empty");
+    memcpy(x_out, pool[0].x.data(), (size_t)m * sizeof(float));
+    res->best_value = pool[0].v;
+    res->best_index = -1;                                  // the point is not a member of one indexed set
+    res->n_evals = evals;
+    res->n_tie_evals = 0;
+    if (best_response_out) memcpy(best_response_out, pool[0].br.data(), (size_t)K * sizeof(int32_t));
     return BSSE_OK;
 }
 

@@ -80,3 +80,29 @@ def test_topk_then_local_resweep_on_the_hand_game():
             bsse.bsse_lattice_around(g, 64, keep, radius)        # the set the next round refines
             radius *= 0.25
         assert best > 3.49
+
+
+def test_refine_driver_on_the_hand_game_and_config1():
+    """bsse_refine is the same loop in the library.  Hand game: from the resolution-5 lattice (3.4)
+    to above 3.49, never above 3.5.  Config 1 against the exact equilibrium value of the LP module."""
+    from oracle import sse_lp
+    A = np.array([[[2, 4], [1, 3]]], np.float32)
+    B = np.array([[[1, 0], [0, 1]]], np.float32)
+    with bsse.bsse_create(2, 2, 1, A, B, np.ones(1, np.float32)) as g:
+        bsse.bsse_lattice(g, 5)
+        x, v, br, evals = bsse.bsse_refine(g, 2, 3, lattice_N=64, radius=0.25, shrink=0.25)
+        assert 3.49 < v <= 3.5 + 1e-6 and br[0] == 1 and evals > 0
+        assert abs(float(x.sum()) - 1.0) < 1e-6 and abs(v - (3.0 + float(x[0]))) < 1e-5
+        bsse.bsse_lattice(g, 5)
+        x2, v2, _, _ = bsse.bsse_refine(g, 2, 3, cloud_count=500, seed=9, radius=0.25, shrink=0.5)
+        assert 3.4 - 1e-6 <= v2 <= 3.5 + 1e-6
+        with pytest.raises(bsse.BsseError):
+            bsse.bsse_refine(g, 2, 1, lattice_N=4, cloud_count=4)
+    game = workloads.game(1)
+    v_sse, _, _ = sse_lp.solve(game.A, game.B, game.prior)
+    with _make(game) as g:
+        bsse.bsse_lattice(g, 7)
+        coarse = bsse.bsse_sweep(g)
+        x, v, br, _ = bsse.bsse_refine(g, 3, 4, lattice_N=12, radius=0.3, shrink=0.3)
+    assert coarse.best_value - 1e-7 <= v <= v_sse + 1e-5
+    assert v >= v_sse - 5e-3 * max(1.0, abs(v_sse))
