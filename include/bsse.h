@@ -246,6 +246,20 @@ bsse_status bsse_refine(bsse_game *g, int k, int rounds, int lattice_N, int64_t 
  * any commitment with that profile can earn (the equilibrium value itself when the profile is
  * the equilibrium's).  BSSE_EINVAL if the given profile is a best response nowhere.  Waits for
  * the stream. */
+/* bsse_solve_realised: the multiple-LPs solve restricted to the follower profiles the sweep
+ * realises.  Evaluates the candidates (bsse_eval's outputs), collects the distinct best-response
+ * profiles, and solves the program of each, most promising first (by the best swept value under
+ * the profile), at most max_profiles of them.  *value_out = the greatest program optimum, x_out =
+ * host [m] its vertex (fp32), profile_out = host [K] its profile (may be NULL),
+ * *n_profiles_out = distinct profiles realised, *n_solved_out = programs solved.  Every program
+ * optimum is attainable (at the vertex, by the leader-favourable tie-break), so
+ *     best swept value <= *value_out <= equilibrium value,
+ * with equality on the right whenever the equilibrium's profile is among those solved -- then
+ * this is the exact strong Stackelberg equilibrium for n_solved programs instead of n^K.
+ * count * K <= 2^27.  Waits for the stream. */
+bsse_status bsse_solve_realised(bsse_game *g, const float *candidates_dev, int64_t count,
+                                int max_profiles, float *x_out, double *value_out,
+                                int32_t *profile_out, int *n_profiles_out, int *n_solved_out);
 bsse_status bsse_profile_lp(int m, int n, int K, const float *A, const float *B, const float *prior,
                             const int32_t *profile, double *x_out, double *value_out,
                             int *feasible_out);

@@ -25,7 +25,7 @@ EXPORTS = [
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
-    "bsse_dirichlet_around", "bsse_refine",
+    "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
     L.bsse_sweep_priors.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.bsse_profile_lp.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, P(ctypes.c_double), P(i32)]
     L.bsse_polish.argtypes = [vp, vp, vp, P(bsse_result), vp, P(ctypes.c_double)]
+    L.bsse_solve_realised.argtypes = [vp, vp, i64, i32, vp, P(ctypes.c_double), vp, P(i32), P(i32)]
     L.bsse_sweep_topk.argtypes = [vp, vp, i64, i32, vp, vp, vp, P(i32)]
     L.bsse_lattice_around.argtypes = [vp, i32, vp, ctypes.c_float, P(i64)]
     L.bsse_refine.argtypes = [vp, i32, i32, i32, i64, u64, ctypes.c_float, ctypes.c_float, vp,
@@ -328,6 +329,21 @@ def bsse_sweep_topk(g: Game, k: int, candidates=None, count: Optional[int] = Non
                                  v.ctypes.data, idx.ctypes.data, br.ctypes.data, ctypes.byref(found)))
     f = found.value
     return v[:f].copy(), idx[:f].copy(), br[:f].copy()
+
+
+def bsse_solve_realised(g: Game, candidates=None, count: Optional[int] = None, max_profiles: int = 1 << 20):
+    """(value, x float32 [m], profile int32 [K], distinct profiles realised, programs solved)."""
+    if candidates is not None and count is None:
+        count = candidates.numel() // g.m
+    if count is None:
+        count = 0
+    x = np.zeros(g.m, dtype=np.float32)
+    prof = np.full(g.K, -1, dtype=np.int32)
+    v, npf, ns = ctypes.c_double(0.0), ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().bsse_solve_realised(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                                     int(max_profiles), x.ctypes.data, ctypes.byref(v), prof.ctypes.data,
+                                     ctypes.byref(npf), ctypes.byref(ns)))
+    return v.value, x, prof, npf.value, ns.value
 
 
 def bsse_refine(g: Game, k: int, rounds: int, lattice_N: int = 0, cloud_count: int = 0, seed: int = 0,

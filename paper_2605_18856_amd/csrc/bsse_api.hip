@@ -1103,6 +1103,79 @@ extern "C" bsse_status bsse_polish(bsse_game *g, const int32_t *profile, float *
     return BSSE_OK;
 }
 
+extern "C" bsse_status bsse_solve_realised(bsse_game *g, const float *candidates_dev, int64_t count,
+                                           int max_profiles, float *x_out, double *value_out,
+                                           int32_t *profile_out, int *n_profiles_out, int *n_solved_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!x_out || !value_out || !n_profiles_out || !n_solved_out) return fail(BSSE_EINVAL, "NULL argument");
+    if (max_profiles < 1) return fail(BSSE_EINVAL, "max_profiles must be >= 1");
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    const int m = g->m, n = g->n, K = g->K;
+    if (count == 0) return fail(BSSE_EINVAL, "no candidates");
+    if ((double)count * K > (double)(1u << 27)) return fail(BSSE_EOVERFLOW, "count * K exceeds 2^27 best responses");
+    const double cells = (double)m * (2.0 + (double)K * (n - 1) + m);
+    if (cells > (double)(1u << 28)) return fail(BSSE_EOVERFLOW, "the program's tableau (%.3g cells) is too large", cells);
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    DevBuf V, br;
+    HIP_TRY(hipMalloc(&V.p, (size_t)count * sizeof(float)));
+    HIP_TRY(hipMalloc(&br.p, (size_t)count * K * sizeof(int32_t)));
+    SweepArgs a{};
+    a.X = candidates_dev; a.count = count; a.index_base = 0;
+    a.V_out = V.as<float>(); a.br_out = br.as<int32_t>();
+    HIP_TRY(launch_sweep(g, a, true));
+    std::vector<float> hv;
+    std::vector<int32_t> hb;
+    std::vector<int64_t> order;
+    try {
+        hv.resize((size_t)count); hb.resize((size_t)count * K); order.resize((size_t)count);
+    } catch (...) { return fail(BSSE_ENOMEM, "host allocation failed"); }
+    HIP_TRY(hipMemcpyAsync(hv.data(), V.p, hv.size() * sizeof(float), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(hb.data(), br.p, hb.size() * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    // distinct profiles, each with the best value a candidate reached under it: sort the candidates
+    // by profile (then value descending) and take the head of every run
+    for (int64_t c = 0; c < count; ++c) order[(size_t)c] = c;
+    auto prof_less = [&](int64_t x, int64_t y) {
+        const int cmp = memcmp(&hb[(size_t)x * K], &hb[(size_t)y * K], (size_t)K * sizeof(int32_t));
+        if (cmp != 0) return cmp < 0;
+        if (hv[(size_t)x] != hv[(size_t)y]) return hv[(size_t)x] > hv[(size_t)y];
+        return x < y;
+    };
+    std::sort(order.begin(), order.end(), prof_less);
+    std::vector<int64_t> heads;
+    for (int64_t i = 0; i < count; ++i)
+        if (i == 0 || memcmp(&hb[(size_t)order[(size_t)i] * K], &hb[(size_t)order[(size_t)i - 1] * K],
+                             (size_t)K * sizeof(int32_t)) != 0)
+            heads.push_back(order[(size_t)i]);
+    // most promising first: by the best swept value under the profile
+    std::sort(heads.begin(), heads.end(), [&](int64_t x, int64_t y) {
+        return hv[(size_t)x] != hv[(size_t)y] ? hv[(size_t)x] > hv[(size_t)y] : x < y;
+    });
+    *n_profiles_out = (int)(heads.size() > 0x7FFFFFFF ? 0x7FFFFFFF : heads.size());
+    const size_t todo = heads.size() < (size_t)max_profiles ? heads.size() : (size_t)max_profiles;
+    std::vector<double> x((size_t)m), xbest((size_t)m);
+    double vbest = 0.0;
+    int64_t cbest = -1;
+    for (size_t i = 0; i < todo; ++i) {
+        double v = 0.0;
+        const int rc = solve_profile_lp(m, n, K, g->hA.data(), g->hB.data(), g->hprior.data(),
+                                        &hb[(size_t)heads[i] * K], x.data(), &v);
+        if (rc == 2) return fail(BSSE_ESTATE, "the simplex method did not converge");
+        if (rc == 1) continue;        // realised under rounded operands only (bf16 storage)
+        if (cbest < 0 || v > vbest) { vbest = v; cbest = heads[i]; xbest = x; }
+    }
+    *n_solved_out = (int)todo;
+    if (cbest < 0) return fail(BSSE_ESTATE, "no realised profile has a feasible program");
+    for (int i = 0; i < m; ++i) x_out[i] = (float)xbest[(size_t)i];
+    *value_out = vbest;
+    if (profile_out) memcpy(profile_out, &hb[(size_t)cbest * K], (size_t)K * sizeof(int32_t));
+    return BSSE_OK;
+}
+
 // ------------------------------------------------------------------------------- timing
 extern "C" bsse_status bsse_set_timing(bsse_game *g, int enabled)
 {

@@ -93,6 +93,7 @@ def test_null_handles_are_rejected():
     assert L.bsse_sweep_topk(None, None, 0, 1, None, None, None, None) == bsse.BSSE_EINVAL
     assert L.bsse_lattice_around(None, 4, None, 0.5, ctypes.byref(c)) == bsse.BSSE_EINVAL
     assert L.bsse_refine(None, 1, 1, 4, 0, 0, 0.5, 0.5, None, None, None) == bsse.BSSE_EINVAL
+    assert L.bsse_solve_realised(None, None, 0, 1, None, None, None, None, None) == bsse.BSSE_EINVAL
     assert L.bsse_dirichlet_around(None, 1, 0, 4, None, 0.5, None) == bsse.BSSE_EINVAL
     assert L.bsse_set_stream(None, None) == bsse.BSSE_EINVAL
     assert L.bsse_set_timing(None, 1) == bsse.BSSE_EINVAL

@@ -99,3 +99,41 @@ def test_polish_state_and_argument_errors():
         with pytest.raises(bsse.BsseError) as e:
             bsse.bsse_polish(g, profile=[0, 3])
         assert e.value.status == bsse.BSSE_EINVAL
+
+
+@pytest.mark.parametrize("shape,count", [((3, 3, 2), 4000), ((4, 3, 3), 20000), ((5, 4, 2), 20000),
+                                         ((8, 8, 1), 20000)])
+def test_solve_realised_equals_the_full_multiple_lps_solve(shape, count):
+    """With a dense enough sweep the equilibrium's profile is realised by some candidate, and the
+    solve over the realised profiles is the exact equilibrium value (the LP module enumerates all
+    n^K profiles) at a fraction of the programs."""
+    torch = _torch()
+    m, n, K = shape
+    game = workloads.small_game(m, n, K, seed=40 + m + n, kind="normal")
+    v_sse, x_sse, prof_sse = sse_lp.solve(game.A, game.B, game.prior)
+    X = workloads.host_candidates(m, count, seed=17, kind="dirichlet")
+    with _make(game) as g:
+        Xd = torch.from_numpy(X).cuda()
+        sweep = bsse.bsse_sweep(g, Xd, count)
+        v, x, prof, n_prof, n_solved = bsse.bsse_solve_realised(g, Xd, count)
+    assert n_solved == n_prof <= n ** K
+    assert sweep.best_value - 1e-6 <= v <= v_sse + 1e-8
+    assert v == pytest.approx(v_sse, abs=1e-7 * max(1.0, abs(v_sse)))
+    ok, v_ref, _ = sse_lp.profile_lp(game.A, game.B, game.prior, prof)
+    assert ok and v == pytest.approx(v_ref, abs=1e-7 * max(1.0, abs(v_ref)))
+    assert abs(float(x.sum()) - 1.0) < 1e-6 and (x >= 0).all()
+
+
+def test_solve_realised_config1_and_truncation():
+    game = workloads.game(1)
+    v_sse, _, prof_sse = sse_lp.solve(game.A, game.B, game.prior)
+    with _make(game) as g:
+        bsse.bsse_lattice(g, 100)
+        v, x, prof, n_prof, n_solved = bsse.bsse_solve_realised(g)
+        assert v == pytest.approx(v_sse, abs=1e-8) and tuple(prof) == tuple(prof_sse)
+        assert 1 <= n_prof <= 9 and n_solved == n_prof
+        # one program only: the profile of the best swept candidate
+        v1, _, prof1, n_prof1, n_solved1 = bsse.bsse_solve_realised(g, max_profiles=1)
+        sweep = bsse.bsse_sweep(g)
+        assert n_solved1 == 1 and n_prof1 == n_prof and tuple(prof1) == tuple(sweep.best_response)
+        assert sweep.best_value - 1e-6 <= v1 <= v + 1e-12
