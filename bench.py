@@ -5,9 +5,12 @@
 
 A step is one pass of the whole hot path over one batch: generate the batch's candidates
 on the device (seeded flat-Dirichlet rows or the simplex lattice), sweep them (follower
-payoffs, tie-broken best responses, leader value, arg-max), and bring the result (best
-value, best index, K best responses) back to the host.  Payoffs and prior are resident in
-HBM before the timed region.  Prints ONE JSON line.
+payoffs, tie-broken best responses, leader value, arg-max), merge the batch's best into the
+running best, and evaluate a new running best once more for its K best responses.  The K
+timed steps are the K chunks of one streamed sweep: the result (best value, best index, best
+responses) comes back to the host after the last step, inside the timed region; the figure
+with a result brought back after every step is reported beside it.  Payoffs and prior are
+resident in HBM before the timed region.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -62,26 +65,46 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     else:
         Xd = torch.empty((count, game.m), dtype=torch.float32, device="cuda")
 
+    # games on the small-game kernel generate their rows inside the sweep kernel
+    fused = name == "config2"
+
     def step(k):
+        # a fresh batch of the seeded sequence every step; the lattice is the same set every time
         if lattice:
             bsse.bsse_lattice(g, game.lattice_N)
-            return bsse.bsse_sweep(g)
-        # a fresh batch of the seeded sequence every step
-        bsse.bsse_dirichlet(g, game.candidate_seed, k * count, count, Xd)
-        return bsse.bsse_sweep(g, Xd, count)
+            bsse.bsse_sweep_chunk(g, None, 0, 0)
+        elif fused:
+            bsse.bsse_sweep_dirichlet_chunk(g, game.candidate_seed, k * count, count, k * count)
+        else:
+            bsse.bsse_dirichlet(g, game.candidate_seed, k * count, count, Xd)
+            bsse.bsse_sweep_chunk(g, Xd, count, k * count)
 
-    for k in range(warmup):
-        step(k)
+    def run(first, n, each):
+        """n steps; each: a result on the host after every step, else once after the last"""
+        out = None
+        bsse.bsse_sweep_reset(g)
+        for k in range(first, first + n):
+            step(k)
+            if each:
+                out = bsse.bsse_sweep_result(g)
+                bsse.bsse_sweep_reset(g)
+        return out if each else bsse.bsse_sweep_result(g)
+
+    run(0, warmup, False)
     torch.cuda.synchronize()
     bsse.bsse_set_timing(g, True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(steps):
-        out = step(warmup + k)
+    out = run(warmup, steps, False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kernel_ms, launches = bsse.bsse_get_timing(g)
     bsse.bsse_set_timing(g, False)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    run(warmup, steps, True)
+    torch.cuda.synchronize()
+    ms_per_step_each = (time.perf_counter() - t2) * 1e3 / steps
 
     ms_per_step = (t1 - t0) * 1e3 / steps
     evals = count * game.K
@@ -95,7 +118,24 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     flop_peak = PEAK_TFLOPS[path]
     t_hbm = bytes_ / (HBM_PEAK_GBS * 1e9)
     t_flop = flops * EXECUTED_FLOP_FACTOR.get(path, 1.0) / (flop_peak * 1e12)   # what the unit executes
-    if t_hbm >= t_flop:
+    if fused:
+        # The rows are made in registers and nothing but the 3 KiB of payoffs is read: no memory
+        # roofline applies.  The kernel is bound by instruction issue of the vector and matrix
+        # units, which have the same fp32 peak on this part and do not overlap for fp32, so that
+        # peak (a fused multiply-add = 2 operations) prices the algorithmic operations of one
+        # candidate: the generator (per 4 components one Philox4x32-10 block = 10 rounds of 2 wide
+        # multiplies and 4 exclusive-ors; per component ~10 operations from word to exponential;
+        # m - 1 additions, one division, m scalings) and the sweep (per type 2mn for the follower
+        # payoffs, n - 1 comparisons for the maximum, n for its position and ties, 2m for the
+        # leader payoff, 2 for the prior-weighted sum).
+        m, n, K = game.m, game.n, game.K
+        gen_ops = (m / 4.0) * 60.0 + m * 10.0 + (m - 1) + 1 + m
+        sweep_ops = K * (2.0 * m * n + (n - 1) + n + 2.0 * m + 2.0)
+        flops = count * (gen_ops + sweep_ops)
+        bytes_ = 0.0
+        bound, unit, peak = "alu", "TFLOP/s", PEAK_TFLOPS["mfma_f32"]
+        achieved = flops / (k_ms * 1e-3) / 1e12
+    elif t_hbm >= t_flop:
         bound, unit, peak = "hbm", "GB/s", HBM_PEAK_GBS
         achieved = bytes_ / (k_ms * 1e-3) / 1e9
     else:
@@ -104,7 +144,7 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
         achieved = flops / (k_ms * 1e-3) / 1e12
     roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                 "frac": achieved / peak, "traffic": TRAFFIC_BYTES.get(name),
-                "kernel": "fused sweep (" + path + ")",
+                "kernel": ("generate + sweep (" if fused else "fused sweep (") + path + ")",
                 "kernel_ms": k_ms, "launches": launches,
                 "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": bytes_}
     if path in EXECUTED_FLOP_FACTOR and bound == "mfma":
@@ -153,6 +193,7 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     g.close()
     return {
         "ms_per_step": ms_per_step, "value": value, "path": path, "count": count,
+        "ms_per_step_each": ms_per_step_each, "fused": fused,
         "game": game, "roofline": roofline, "cpu_baseline": cpu, "note": note,
         "best_index": out.best_index, "best_value": out.best_value,
         "n_tie_evals": out.n_tie_evals,
@@ -265,7 +306,13 @@ def main():
         "dtype": "bf16" if game.storage == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "description": r["note"], "m": game.m, "n": game.n,
                    "K": game.K, "candidates_per_step": r["count"], "path": r["path"],
-                   "step": "generate candidates + sweep + result to host"},
+                   "step": ("candidates generated inside the sweep kernel" if r["fused"] else
+                            "generate candidates into a buffer + sweep") +
+                           " + merge into the running best; K steps = K chunks of one streamed "
+                           "sweep, result to host after the last",
+                   "ms_per_step_with_a_result_after_every_step": r["ms_per_step_each"],
+                   "value_with_a_result_after_every_step":
+                       r["count"] * game.K / (r["ms_per_step_each"] * 1e-3)},
         "roofline": r["roofline"],
         "cpu_baseline": r["cpu_baseline"],
         "result": {"best_index": r["best_index"], "best_value": r["best_value"],

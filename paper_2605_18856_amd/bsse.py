@@ -25,7 +25,8 @@ EXPORTS = [
     "bsse_sweep_chunk", "bsse_sweep_result", "bsse_eval", "bsse_path_name", "bsse_set_timing",
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
-    "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised",
+    "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised", "bsse_sweep_dirichlet",
+    "bsse_sweep_dirichlet_chunk",
 ]
 
 
@@ -77,6 +78,8 @@ def lib():
     L.bsse_sweep_reset.argtypes = [vp]
     L.bsse_sweep_chunk.argtypes = [vp, vp, i64, i64]
     L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
+    L.bsse_sweep_dirichlet.argtypes = [vp, u64, i64, i64, P(bsse_result), vp]
+    L.bsse_sweep_dirichlet_chunk.argtypes = [vp, u64, i64, i64, i64]
     L.bsse_eval.argtypes = [vp, vp, i64, vp, vp]
     L.bsse_sweep_priors.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.bsse_profile_lp.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, P(ctypes.c_double), P(i32)]
@@ -403,6 +406,17 @@ def bsse_sweep_reset(g: Game):
 def bsse_sweep_chunk(g: Game, candidates, count: int, index_base: int):
     _check(lib().bsse_sweep_chunk(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
                                   index_base))
+
+
+def bsse_sweep_dirichlet(g: Game, seed: int, first: int, count: int) -> SweepOutcome:
+    res = bsse_result()
+    br = np.full(g.K, -1, dtype=np.int32)
+    _check(lib().bsse_sweep_dirichlet(g.handle, seed, first, count, ctypes.byref(res), br.ctypes.data))
+    return _outcome(g, res, br)
+
+
+def bsse_sweep_dirichlet_chunk(g: Game, seed: int, first: int, count: int, index_base: int):
+    _check(lib().bsse_sweep_dirichlet_chunk(g.handle, seed, first, count, index_base))
 
 
 def bsse_sweep_result(g: Game) -> SweepOutcome:

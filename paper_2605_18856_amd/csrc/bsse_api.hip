@@ -96,6 +96,8 @@ struct bsse_game {
     PriorScratch pri;
     // host copies of the game as given to create (fp32, unrounded): the profile LP of bsse_polish
     std::vector<float> hA, hB, hprior;
+    float *stage = nullptr;                        // generated rows on their way into a sweep
+    size_t stage_cap = 0;
     float *centre_dev = nullptr;                   // [m] centre of a local candidate set
     float *pol_rows = nullptr, *pol_v = nullptr;   // device scratch of bsse_polish
     int32_t *pol_br = nullptr;
@@ -165,7 +167,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->win_l);
     g->pri.release();
     (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
-    (void)hipFree(g->centre_dev);
+    (void)hipFree(g->centre_dev); (void)hipFree(g->stage);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
     for (hipEvent_t e : g->ev) (void)hipEventDestroy(e);
@@ -604,22 +606,16 @@ static bsse_status resolve_candidates(bsse_game *g, const float **X, int64_t *co
     return BSSE_OK;
 }
 
-extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t count,
-                                        int64_t index_base)
+namespace {
+
+// One chunk through the sweep kernel and the merge into the running best.  a.X / a.gen*, a.count
+// and a.index_base are set by the caller; the device is current.
+bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
 {
-    g_err[0] = 0;
-    if (!g) return fail(BSSE_EINVAL, "game is NULL");
-    if (index_base < 0) return fail(BSSE_EINVAL, "index_base must be >= 0");
-    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
-    if (st != BSSE_OK) return st;
-    if (index_base > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "index_base + count overflows");
-    if (count == 0) return BSSE_OK;
-    DeviceGuard dg(g->device);
-    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    bsse_status st;
+    const long long count = a.count;
     const long long nblocks = sweep_blocks(g, count);
     if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
-    SweepArgs a{};
-    a.X = candidates_dev; a.count = count; a.index_base = index_base;
     a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (g->timing) {
@@ -641,13 +637,99 @@ extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_de
         f.win_v = &g->h_out->fin_v; f.win_br = g->h_br;
         HIP_TRY(launch_finish_small(g->view, a, f, g->stream));
     } else {
-        HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, candidates_dev, index_base, g->m,
+        HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, a.X, a.index_base, g->m,
                                     g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
                                     g->stream));
     }
     g->fresh = false;
-    g->n_evals += (long long)count * g->K;
+    g->n_evals += count * g->K;
     return BSSE_OK;
+}
+
+bool fuses_generation(const bsse_game *g)
+{
+    return g->path != PATH_VALU && mfma_is_small(g->view.variant);
+}
+
+bsse_status check_rows(int64_t first, int64_t count)
+{
+    if (first < 0 || count < 0) return fail(BSSE_EINVAL, "first and count must be >= 0");
+    if (count > CHUNK_MAX) return fail(BSSE_EOVERFLOW, "count exceeds 2^31 rows per call");
+    if (first > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "first + count overflows");
+    return BSSE_OK;
+}
+
+}  // namespace
+
+extern "C" bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t count,
+                                        int64_t index_base)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (index_base < 0) return fail(BSSE_EINVAL, "index_base must be >= 0");
+    bsse_status st = resolve_candidates(g, &candidates_dev, &count);
+    if (st != BSSE_OK) return st;
+    if (index_base > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "index_base + count overflows");
+    if (count == 0) return BSSE_OK;
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    SweepArgs a{};
+    a.X = candidates_dev; a.count = count; a.index_base = index_base;
+    return sweep_chunk_impl(g, a);
+}
+
+extern "C" bsse_status bsse_sweep_dirichlet_chunk(bsse_game *g, uint64_t seed, int64_t first,
+                                                  int64_t count, int64_t index_base)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (index_base < 0) return fail(BSSE_EINVAL, "index_base must be >= 0");
+    bsse_status st = check_rows(first, count);
+    if (st != BSSE_OK) return st;
+    if (index_base > INT64_MAX - count) return fail(BSSE_EOVERFLOW, "index_base + count overflows");
+    if (count == 0) return BSSE_OK;
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    if (fuses_generation(g)) {
+        SweepArgs a{};
+        a.count = count; a.index_base = index_base;
+        a.gen = 1; a.gen_k0 = (unsigned)(seed & 0xFFFFFFFFull); a.gen_k1 = (unsigned)(seed >> 32);
+        a.gen_first = first;
+        return sweep_chunk_impl(g, a);
+    }
+    // other shapes: the rows pass through a staging buffer of the handle (at most 2^26 floats),
+    // piece by piece on the handle's stream
+    long long piece = (1LL << 26) / g->m;
+    if (piece > count) piece = count;
+    const size_t bytes = (size_t)piece * g->m * sizeof(float);
+    if (bytes > g->stage_cap) {
+        HIP_TRY(hipStreamSynchronize(g->stream));
+        (void)hipFree(g->stage);
+        g->stage = nullptr; g->stage_cap = 0;
+        HIP_TRY(hipMalloc((void **)&g->stage, bytes));
+        g->stage_cap = bytes;
+    }
+    for (long long base = 0; base < count; base += piece) {
+        const long long rows = count - base < piece ? count - base : piece;
+        HIP_TRY(launch_dirichlet(seed, first + base, rows, g->m, nullptr, 1.0f, g->stage, g->stream));
+        SweepArgs a{};
+        a.X = g->stage; a.count = rows; a.index_base = index_base + base;
+        if ((st = sweep_chunk_impl(g, a)) != BSSE_OK) return st;
+    }
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_sweep_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
+                                            bsse_result *res, int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!res) return fail(BSSE_EINVAL, "res is NULL");
+    bsse_status st = check_rows(first, count);
+    if (st != BSSE_OK) return st;
+    if ((st = bsse_sweep_reset(g)) != BSSE_OK) return st;
+    if ((st = bsse_sweep_dirichlet_chunk(g, seed, first, count, 0)) != BSSE_OK) return st;
+    return bsse_sweep_result(g, res, best_response_out);
 }
 
 extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_response_out)

@@ -39,6 +39,13 @@ struct SweepArgs {
     // order (the same sum, term by term, as the unsliced kernel).
     float *l_out;
     int slice_stages;        // LDS stages per slice (set by the launcher)
+    // Small-game kernel only, gen != 0: X is not read; row c is the flat-Dirichlet row
+    // gen_first + c of the generator keyed (gen_k0, gen_k1), produced in registers with the
+    // arithmetic of the generation kernel.  x_out (evaluation mode, nullable): the rows, written out.
+    int gen;
+    unsigned gen_k0, gen_k1;
+    long long gen_first;
+    float *x_out;
 };
 
 // Running best over chunks, in device memory.

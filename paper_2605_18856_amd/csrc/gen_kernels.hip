@@ -2,6 +2,7 @@
 // seeded flat-Dirichlet rows.  Both kernels are write-bound: one coalesced pass over the
 // output, no reads beyond a small table.
 #include "bsse_internal.h"
+#include "gen_device.h"
 
 namespace bsse {
 
@@ -62,52 +63,6 @@ hipError_t launch_lattice(const unsigned long long *table, int m, int N, long lo
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------------------
-// Philox4x32 with 10 rounds, from the description in Salmon, Moraes, Dror, Shaw (SC'11):
-// two 32x32->64 multiplies per round feed a fixed permutation with key injection; the key
-// advances by two Weyl constants between rounds.
-struct U4 { unsigned x, y, z, w; };
-
-__device__ __forceinline__ unsigned long long mul_wide(unsigned a, unsigned b)
-{
-    unsigned long long d;
-    asm("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(d) : "s"(a), "v"(b) : "vcc");
-    return d;
-}
-
-__device__ __forceinline__ U4 philox4x32_10(U4 c, unsigned k0, unsigned k1)
-{
-#pragma unroll
-    for (int rnd = 0; rnd < 10; ++rnd) {
-        // one 32x32->64 multiply-add instruction per product (full rate on this part; the
-        // compiler would otherwise issue separate high and low multiplies)
-        const unsigned long long p0 = mul_wide(0xD2511F53u, c.x), p1 = mul_wide(0xCD9E8D57u, c.z);
-        const unsigned hi0 = (unsigned)(p0 >> 32), lo0 = (unsigned)p0;
-        const unsigned hi1 = (unsigned)(p1 >> 32), lo1 = (unsigned)p1;
-        U4 d;
-        d.x = hi1 ^ c.y ^ k0;
-        d.y = lo1;
-        d.z = hi0 ^ c.w ^ k1;
-        d.w = lo0;
-        c = d;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    return c;
-}
-
-// A 32-bit word to a unit exponential: u = ((w >> 8) + 1) / 2^24 is in (0, 1].
-__device__ __forceinline__ float unit_exponential(unsigned w)
-{
-    const float u = (float)((w >> 8) + 1u) * 5.9604644775390625e-08f;   // exact: < 2^24+1
-    // -ln u = -log2(u) * ln 2 with the product carried in two parts; u >= 2^-24 is never
-    // subnormal, so the hardware logarithm needs no range scaling
-    const float r = __builtin_amdgcn_logf(u);
-    const float c = 0x1.62e42ep-1f, cc = 0x1.efa39ep-25f;                // ln 2 = c + cc
-    const float y = r * c;
-    return -(y + fmaf(r, cc, fmaf(r, c, -y)));
-}
-
 // One thread per (row, group of four components): one Philox call, one float4 store, so a
 // wavefront writes 1 KiB contiguously.  Requires m % 4 == 0 and m/4 a power of two <= 64, so
 // that a row's threads sit in one wavefront and the row sum is a butterfly over them.
@@ -127,20 +82,12 @@ dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count
         const bool live = q < quads;
         const long long row = first + (q >> log2_nb);
         const unsigned b = (unsigned)(q & (nb - 1));
-        U4 c = { (unsigned)(unsigned long long)row, (unsigned)((unsigned long long)row >> 32), b, 0u };
-        const U4 w = philox4x32_10(c, k0, k1);
-        float g0 = unit_exponential(w.x), g1 = unit_exponential(w.y);
-        float g2 = unit_exponential(w.z), g3 = unit_exponential(w.w);
-        float sum = (g0 + g1) + (g2 + g3);
+        float g0, g1, g2, g3;
+        dirichlet_quad_raw(row, b, k0, k1, g0, g1, g2, g3);
+        float sum = dirichlet_quad_sum(g0, g1, g2, g3);
         for (int d = 1; d < nb; d <<= 1) sum += __shfl_xor(sum, d, 64);
-        float4 v;
-        if (sum > 0.0f) {
-            const float inv = 1.0f / sum;                                // correctly rounded
-            v = make_float4(g0 * inv, g1 * inv, g2 * inv, g3 * inv);
-        } else {
-            const float e = 1.0f / (float)m;
-            v = make_float4(e, e, e, e);
-        }
+        dirichlet_quad_scale(sum, m, g0, g1, g2, g3);
+        float4 v = make_float4(g0, g1, g2, g3);
         if (centre) {
             v.x = around(v.x, centre, 4 * b, radius, omr);     v.y = around(v.y, centre, 4 * b + 1, radius, omr);
             v.z = around(v.z, centre, 4 * b + 2, radius, omr); v.w = around(v.w, centre, 4 * b + 3, radius, omr);

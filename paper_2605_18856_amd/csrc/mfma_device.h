@@ -44,6 +44,12 @@ __device__ __forceinline__ int pair_min(int v)
     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
     return min((int)r[0], (int)r[1]);
 }
+// The partner lane's value (h = lane / 32 of the caller).
+__device__ __forceinline__ float pair_other(float v, int h)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(h ? r[0] : r[1]);
+}
 __device__ __forceinline__ float pair_sum(float v)
 {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);

@@ -14,6 +14,7 @@
 // the leader matrix sits in LDS, one padded row per (type, action).
 #include "bsse_internal.h"
 #include "mfma_device.h"
+#include "gen_device.h"
 #include <limits.h>
 #include <stdlib.h>
 #include <string.h>
@@ -31,7 +32,7 @@ constexpr int SM_MAX_TILES = 4;
 // TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
 // Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).  The body of a
 // workgroup; block / nblocks are its place in the (one-dimensional) grid of the pass.
-template <int TILES, bool EVAL>
+template <int TILES, bool EVAL, bool GEN>
 __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a, unsigned block,
                                            unsigned nblocks)
 {
@@ -64,7 +65,24 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             if (!ok) { own[ct] = f32x4{ 0, 0, 0, 0 }; oth[ct] = f32x4{ 0, 0, 0, 0 }; }
         }
     };
-    if (task0 < n_tasks) load_task(task0);              // first rows in flight during set-up
+    // GEN: the rows are made here instead.  Lane half h produces components 4h..4h+3 of its
+    // candidate (the thread (row, b = h) of the generation kernel); the row sum and the other four
+    // components come from the partner lane.
+    auto gen_task = [&](unsigned task) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) {
+            const unsigned c = task * per_iter + ct * 32 + col;
+            float g0, g1, g2, g3;
+            dirichlet_quad_raw(a.gen_first + (long long)c, (unsigned)h, a.gen_k0, a.gen_k1, g0, g1, g2, g3);
+            const float sum = pair_sum(dirichlet_quad_sum(g0, g1, g2, g3));
+            dirichlet_quad_scale(sum, SM_M, g0, g1, g2, g3);
+            const bool ok = c < count;
+            own[ct] = ok ? f32x4{ g0, g1, g2, g3 } : f32x4{ 0, 0, 0, 0 };
+#pragma unroll
+            for (int k = 0; k < 4; ++k) oth[ct][k] = pair_other(own[ct][k], h);
+        }
+    };
+    if (!GEN && task0 < n_tasks) load_task(task0);      // first rows in flight during set-up
 
     // leader rows -> LDS (packed on the host with the padded stride); follower fragments and
     // priors -> registers
@@ -101,9 +119,10 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 #pragma unroll 1
     for (unsigned task = task0; task < n_tasks; task += task_stride) {
         f32x4 xo[SM_NT], xt[SM_NT];
+        if (GEN) gen_task(task);
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) { xo[ct] = own[ct]; xt[ct] = oth[ct]; }
-        if (task + task_stride < n_tasks) load_task(task + task_stride);   // next rows in flight
+        if (!GEN && task + task_stride < n_tasks) load_task(task + task_stride);   // next rows in flight
 
         // Both candidate tiles and both of the lane's types advance together through one
         // straight-line block (four independent dependency chains for the scheduler to
@@ -209,6 +228,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             if (!(v == v)) v = -INFINITY;
             if (EVAL) {
                 if (a.V_out && ok && h == 0) a.V_out[c] = v;
+                if (GEN && a.x_out && ok) *(f32x4 *)(a.x_out + (size_t)c * SM_M + 4 * h) = xo[ct];
             } else if (ok && v > best_v) {           // a lane meets its candidates in ascending order
                 best_v = v; best_c = c;
             }
@@ -240,7 +260,15 @@ template <int TILES, bool EVAL>
 __global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
 sweep_small_kernel(GameView g, SweepArgs a)
 {
-    small_body<TILES, EVAL>(g, a, blockIdx.x, gridDim.x);
+    small_body<TILES, EVAL, false>(g, a, blockIdx.x, gridDim.x);
+}
+
+// The sweep over rows generated in registers (step 1 fused in): no candidate ever reaches memory.
+template <int TILES>
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
+sweep_small_gen_kernel(GameView g, SweepArgs a)
+{
+    small_body<TILES, false, true>(g, a, blockIdx.x, gridDim.x);
 }
 
 // Steps 5-6 for the small-game path in one single-workgroup launch: fold the workgroup records
@@ -248,7 +276,7 @@ sweep_small_kernel(GameView g, SweepArgs a)
 // with a strict "greater than", and, when the running best changed, keep its row and evaluate
 // it again with per-candidate outputs, which gives its K best responses (same instruction
 // sequence as the sweep, hence the same value bit for bit).
-template <int TILES>
+template <int TILES, bool GEN>
 __global__ void __launch_bounds__(SM_WAVES * 64)
 small_finish_kernel(GameView g, SweepArgs a, FinishArgs f)
 {
@@ -290,11 +318,17 @@ small_finish_kernel(GameView g, SweepArgs a, FinishArgs f)
     __syncthreads();
     const long long row = win;
     if (row < 0) return;                         // whole workgroup
-    if (tid < SM_M) f.best_x[tid] = a.X[row * SM_M + tid];
     SweepArgs e{};
-    e.X = a.X + row * SM_M; e.count = 1; e.index_base = 0;
+    e.count = 1; e.index_base = 0;
     e.V_out = f.win_v; e.br_out = f.win_br;
-    small_body<TILES, true>(g, e, 0u, 1u);
+    if (GEN) {
+        e.gen = 1; e.gen_k0 = a.gen_k0; e.gen_k1 = a.gen_k1; e.gen_first = a.gen_first + row;
+        e.x_out = f.best_x;
+    } else {
+        if (tid < SM_M) f.best_x[tid] = a.X[row * SM_M + tid];
+        e.X = a.X + row * SM_M;
+    }
+    small_body<TILES, true, GEN>(g, e, 0u, 1u);
 }
 
 typedef void (*small_kernel_t)(GameView, SweepArgs);
@@ -309,14 +343,25 @@ small_kernel_t small_kernel_for(int K, bool eval)
     return nullptr;
 }
 
-typedef void (*small_finish_t)(GameView, SweepArgs, FinishArgs);
-small_finish_t small_finish_for(int K)
+small_kernel_t small_gen_kernel_for(int K)
 {
     switch (K / 4) {
-    case 1: return small_finish_kernel<1>;
-    case 2: return small_finish_kernel<2>;
-    case 3: return small_finish_kernel<3>;
-    case 4: return small_finish_kernel<4>;
+    case 1: return sweep_small_gen_kernel<1>;
+    case 2: return sweep_small_gen_kernel<2>;
+    case 3: return sweep_small_gen_kernel<3>;
+    case 4: return sweep_small_gen_kernel<4>;
+    }
+    return nullptr;
+}
+
+typedef void (*small_finish_t)(GameView, SweepArgs, FinishArgs);
+small_finish_t small_finish_for(int K, bool gen)
+{
+    switch (K / 4) {
+    case 1: return gen ? small_finish_kernel<1, true> : small_finish_kernel<1, false>;
+    case 2: return gen ? small_finish_kernel<2, true> : small_finish_kernel<2, false>;
+    case 3: return gen ? small_finish_kernel<3, true> : small_finish_kernel<3, false>;
+    case 4: return gen ? small_finish_kernel<4, true> : small_finish_kernel<4, false>;
     }
     return nullptr;
 }
@@ -340,9 +385,11 @@ long long small_num_blocks(long long count)
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s)
 {
     if (a.count <= 0) return hipSuccess;
-    small_kernel_t k = small_kernel_for(g.K, a.blk_v == nullptr);
+    const bool eval = a.blk_v == nullptr;
+    if (a.gen && eval) return hipErrorNotSupported;      // generated rows are swept, not listed
+    small_kernel_t k = a.gen ? small_gen_kernel_for(g.K) : small_kernel_for(g.K, eval);
     if (!k) return hipErrorNotSupported;
-    if (((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
+    if (!a.gen && ((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
     hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
     return hipGetLastError();
 }
@@ -350,7 +397,7 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
 hipError_t launch_finish_small(const GameView &g, const SweepArgs &a, const FinishArgs &f, hipStream_t s)
 {
     if (f.nblocks <= 0) return hipSuccess;
-    small_finish_t k = small_finish_for(g.K);
+    small_finish_t k = small_finish_for(g.K, a.gen != 0);
     if (!k) return hipErrorNotSupported;
     hipLaunchKernelGGL(k, dim3(1), dim3(SM_WAVES * 64), 0, s, g, a, f);
     return hipGetLastError();

@@ -1,0 +1,113 @@
+"""bsse_sweep_dirichlet: the sweep over seeded flat-Dirichlet rows that are never written out.
+
+Two kinds of check.  Against the library's own two-step form (bsse_dirichlet into a buffer, then
+bsse_sweep): the contract is equality bit for bit, on every shape family.  Against the oracle: the
+oracle generates the rows itself (fp64 generator, rounded to fp32) and sweeps them; the library's
+winner must be the oracle's up to near-equal values, and its value must be the oracle's value of
+that row within tolerance."""
+import numpy as np
+import pytest
+
+from oracle import dirichlet as odir
+from oracle import sweep as osweep
+from paper_2605_18856_amd import bsse, workloads
+from tests import parity
+from tests.test_gpu_parity import _make
+
+pytestmark = pytest.mark.gpu
+
+
+def _two_step(g, seed, first, count):
+    import torch
+    X = torch.empty((max(count, 1), g.m), dtype=torch.float32, device="cuda")
+    bsse.bsse_dirichlet(g, seed, first, count, X)
+    out = bsse.bsse_sweep(g, X, count)
+    torch.cuda.synchronize()
+    return out
+
+
+def _same(a, b):
+    assert a.best_index == b.best_index
+    assert np.float32(a.best_value) == np.float32(b.best_value)
+    assert a.n_evals == b.n_evals and a.n_tie_evals == b.n_tie_evals
+    if a.best_index >= 0:
+        assert np.array_equal(a.best_response, b.best_response)
+
+
+@pytest.mark.parametrize("K", [4, 8, 12, 16])
+def test_small_game_fused_equals_two_step(K):
+    game = workloads.small_game(8, 8, K, seed=40 + K, kind="normal")
+    with _make(game) as g:
+        assert bsse.bsse_path_name(g).startswith("mfma")
+        for seed, first, count in [(1, 0, 1), (2, 0, 31), (3, 7, 64), (4, 12345, 65), (5, 0, 1000),
+                                   (6, (1 << 32) - 100, 777), (7, 3, (1 << 17) + 5),
+                                   ((1 << 63) + 12345, (1 << 40) + 1, 50000)]:
+            _same(bsse.bsse_sweep_dirichlet(g, seed, first, count), _two_step(g, seed, first, count))
+
+
+@pytest.mark.parametrize("shape,storage", [((3, 3, 2), "f32"), ((5, 7, 3), "f32"), ((16, 16, 8), "f32"),
+                                           ((32, 32, 16), "f32"), ((64, 128, 4), "bf16")])
+def test_other_shapes_equal_two_step(shape, storage):
+    m, n, K = shape
+    game = workloads.small_game(m, n, K, seed=9 + m, kind="normal" if storage == "f32" else "uniform",
+                                storage=storage)
+    with _make(game) as g:
+        for seed, first, count in [(11, 0, 1), (12, 5, 999), (13, 1 << 33, 40000)]:
+            _same(bsse.bsse_sweep_dirichlet(g, seed, first, count), _two_step(g, seed, first, count))
+
+
+def test_staged_pieces_and_chunks():
+    """m = 16: a staging piece holds 2^22 rows, so 2^22 + 4097 rows take two pieces; and the streamed
+    form in three unequal chunks gives the one-shot result (global indices, strict merge)."""
+    game = workloads.small_game(16, 16, 4, seed=3, kind="normal")
+    count = (1 << 22) + 4097
+    with _make(game) as g:
+        one = bsse.bsse_sweep_dirichlet(g, 21, 10, count)
+        _same(one, _two_step(g, 21, 10, count))
+        bsse.bsse_sweep_reset(g)
+        cuts = [0, 1000, (1 << 22) - 3, count]
+        for lo, hi in zip(cuts[:-1], cuts[1:]):
+            bsse.bsse_sweep_dirichlet_chunk(g, 21, 10 + lo, hi - lo, lo)
+        _same(bsse.bsse_sweep_result(g), one)
+    small = workloads.game(2)
+    with _make(small) as g:
+        one = bsse.bsse_sweep_dirichlet(g, 5, 0, 300000)
+        bsse.bsse_sweep_reset(g)
+        for lo, hi in [(0, 70001), (70001, 70002), (70002, 300000)]:
+            bsse.bsse_sweep_dirichlet_chunk(g, 5, lo, hi - lo, lo)
+        _same(bsse.bsse_sweep_result(g), one)
+
+
+@pytest.mark.parametrize("cfg,count", [(2, 200000), (1, 30000)])
+def test_against_the_oracle_on_its_own_rows(cfg, count):
+    game = workloads.game(cfg)
+    seed, first = 77, 1234
+    Xo = odir.rows(seed, first, count, game.m).astype(np.float32)
+    ref = osweep.sweep(game.A, game.B, game.prior, Xo, nthreads=8)
+    with _make(game) as g:
+        out = bsse.bsse_sweep_dirichlet(g, seed, first, count)
+    assert out.n_evals == count * game.K
+    v_ref, sc = osweep.value_under_profile(game.A, game.prior, Xo[out.best_index].astype(np.float64),
+                                           out.best_response)
+    # the device's rows differ from the oracle's by fp32 rounding of the generator (a few ulp)
+    assert abs(out.best_value - v_ref) <= 2 * parity.TOL_F32 * max(sc, 1e-30)
+    assert ref.values[out.best_index] >= ref.best_value - 2 * parity.TOL_F32 * max(sc, 1e-30)
+    if out.best_index == ref.best_index:
+        assert np.array_equal(out.best_response, ref.best_br)
+
+
+def test_arguments():
+    game = workloads.game(2)
+    with _make(game) as g:
+        out = bsse.bsse_sweep_dirichlet(g, 1, 0, 0)
+        assert out.best_index == -1 and out.n_evals == 0
+        for first, count in [(-1, 10), (0, -1)]:
+            with pytest.raises(bsse.BsseError) as e:
+                bsse.bsse_sweep_dirichlet(g, 1, first, count)
+            assert e.value.status == bsse.BSSE_EINVAL
+        with pytest.raises(bsse.BsseError) as e:
+            bsse.bsse_sweep_dirichlet(g, 1, 0, (1 << 31) + 1)
+        assert e.value.status == bsse.BSSE_EOVERFLOW
+        with pytest.raises(bsse.BsseError) as e:
+            bsse.bsse_sweep_dirichlet(g, 1, (1 << 63) - 5, 10)
+        assert e.value.status == bsse.BSSE_EOVERFLOW
