@@ -170,13 +170,18 @@ bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t 
                              int64_t index_base);
 bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t *best_response_out);
 
+/* The row of the running best (the candidate at best_index of the sweep so far), copied from the
+ * handle: x_out = host [m] fp32.  Waits for the stream.  BSSE_ESTATE if no candidate has been
+ * swept since the last reset. */
+bsse_status bsse_sweep_best_row(bsse_game *g, float *x_out);
+
 /* Steps 1-6 without a candidate buffer: the sweep of rows first..first+count-1 of the seeded
  * flat-Dirichlet sequence (exactly the rows bsse_dirichlet(g, seed, first, count, X) writes; the
  * result is, bit for bit, that of bsse_sweep(g, X, count, ...): row first + r has index r).  For
  * games that run the small-game kernel (m = n = 8, K in {4, 8, 12, 16}, fp32) the rows are produced
  * in registers inside the sweep kernel and never reach memory; for every other game they pass
  * through a staging buffer of the handle (at most 2^26 floats), piece by piece.  The winning
- * row itself is bsse_dirichlet(g, seed, first + best_index, 1, out).
+ * row itself is bsse_sweep_best_row, or bsse_dirichlet(g, seed, first + best_index, 1, out).
  *   bsse_sweep_dirichlet        resets, sweeps, waits and reports like bsse_sweep;
  *   bsse_sweep_dirichlet_chunk  the streamed form, like bsse_sweep_chunk (row first + r has global
  *                               index index_base + r); report with bsse_sweep_result.

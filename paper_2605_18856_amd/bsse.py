@@ -26,7 +26,7 @@ EXPORTS = [
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
     "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised", "bsse_sweep_dirichlet",
-    "bsse_sweep_dirichlet_chunk",
+    "bsse_sweep_dirichlet_chunk", "bsse_sweep_best_row",
 ]
 
 
@@ -78,6 +78,7 @@ def lib():
     L.bsse_sweep_reset.argtypes = [vp]
     L.bsse_sweep_chunk.argtypes = [vp, vp, i64, i64]
     L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
+    L.bsse_sweep_best_row.argtypes = [vp, vp]
     L.bsse_sweep_dirichlet.argtypes = [vp, u64, i64, i64, P(bsse_result), vp]
     L.bsse_sweep_dirichlet_chunk.argtypes = [vp, u64, i64, i64, i64]
     L.bsse_eval.argtypes = [vp, vp, i64, vp, vp]
@@ -406,6 +407,12 @@ def bsse_sweep_reset(g: Game):
 def bsse_sweep_chunk(g: Game, candidates, count: int, index_base: int):
     _check(lib().bsse_sweep_chunk(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
                                   index_base))
+
+
+def bsse_sweep_best_row(g: Game) -> np.ndarray:
+    x = np.empty(g.m, dtype=np.float32)
+    _check(lib().bsse_sweep_best_row(g.handle, x.ctypes.data))
+    return x
 
 
 def bsse_sweep_dirichlet(g: Game, seed: int, first: int, count: int) -> SweepOutcome:

@@ -88,6 +88,8 @@ struct bsse_game {
     size_t lat_table_cap = 0;
     float *blk_v = nullptr;
     long long *blk_i = nullptr;
+    unsigned *blk_br = nullptr;  // [blk_cap][2] packed best responses (small-game kernel)
+    unsigned *done = nullptr;    // finished-workgroup count of the small-game kernel's grid stage
     long long blk_cap = 0;
     RunningBest *run = nullptr;
     float *best_x = nullptr;
@@ -162,7 +164,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->dB); (void)hipFree(g->dAT); (void)hipFree(g->dprior);
     (void)hipFree(g->dBpack); (void)hipFree(g->dATpack);
     (void)hipFree(g->gen); (void)hipFree(g->lat_table);
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->blk_br); (void)hipFree(g->done);
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
     (void)hipFree(g->win_l);
     g->pri.release();
@@ -180,10 +182,11 @@ bsse_status ensure_blocks(bsse_game *g, long long nblocks)
     if (nblocks <= g->blk_cap) return BSSE_OK;
     // the stream may still be reading the old workspace
     HIP_TRY(hipStreamSynchronize(g->stream));
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
-    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_cap = 0;
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->blk_br);
+    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_br = nullptr; g->blk_cap = 0;
     HIP_TRY(hipMalloc((void **)&g->blk_v, (size_t)nblocks * sizeof(float)));
     HIP_TRY(hipMalloc((void **)&g->blk_i, (size_t)nblocks * sizeof(long long)));
+    HIP_TRY(hipMalloc((void **)&g->blk_br, (size_t)nblocks * 2 * sizeof(unsigned)));
     g->blk_cap = nblocks;
     return BSSE_OK;
 }
@@ -373,6 +376,7 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->done, sizeof(unsigned))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->win_l, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
@@ -617,6 +621,14 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
     const long long nblocks = sweep_blocks(g, count);
     if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
     a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
+    const bool small = g->path != PATH_VALU && mfma_is_small(g->view.variant);
+    if (small) {
+        // the grid stage, the merge and the report of a new running best run inside the launch
+        a.fin.first = g->fresh ? 1 : 0;
+        a.fin.run = g->run; a.fin.run_host = &g->h_out->run; a.fin.best_x = g->best_x;
+        a.fin.win_v = &g->h_out->fin_v; a.fin.win_br = g->h_br;
+        a.fin.blk_br = g->blk_br; a.fin.done = g->done;
+    }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (g->timing) {
         if ((st = take_event(g, &e0)) != BSSE_OK) return st;
@@ -629,18 +641,10 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
         g->ev.push_back(e0); g->ev.push_back(e1);
     }
     HIP_TRY(le);
-    if (g->path != PATH_VALU && mfma_is_small(g->view.variant)) {
-        // grid stage, merge and the best responses of a new running best in one launch
-        FinishArgs f{};
-        f.nblocks = nblocks; f.first = g->fresh ? 1 : 0;
-        f.run = g->run; f.run_host = &g->h_out->run; f.best_x = g->best_x;
-        f.win_v = &g->h_out->fin_v; f.win_br = g->h_br;
-        HIP_TRY(launch_finish_small(g->view, a, f, g->stream));
-    } else {
+    if (!small)
         HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, a.X, a.index_base, g->m,
                                     g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
                                     g->stream));
-    }
     g->fresh = false;
     g->n_evals += count * g->K;
     return BSSE_OK;
@@ -764,6 +768,19 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     res->n_evals = g->n_evals;
     res->n_tie_evals = (int64_t)g->h_out->run.ties;
     if (has && best_response_out) memcpy(best_response_out, g->h_br, (size_t)g->K * 4);
+    return BSSE_OK;
+}
+
+extern "C" bsse_status bsse_sweep_best_row(bsse_game *g, float *x_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!x_out) return fail(BSSE_EINVAL, "x_out is NULL");
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    HIP_TRY(hipStreamSynchronize(g->stream));
+    if (g->fresh || !g->h_out->run.has) return fail(BSSE_ESTATE, "no candidate has been swept since the last reset");
+    HIP_TRY(hipMemcpy(x_out, g->best_x, (size_t)g->m * sizeof(float), hipMemcpyDeviceToHost));
     return BSSE_OK;
 }
 

@@ -21,6 +21,28 @@ struct GameView {
     int variant;          // matrix-core kernel variant chosen at create (see mfma_select)
 };
 
+// Running best over chunks, in device memory.
+struct RunningBest {
+    float value;
+    int   has;               // 0 until a chunk has been merged
+    long long index;
+    unsigned long long ties; // tie evaluations of all merged chunks
+};
+
+// Grid stage of a sweep launch inside the small-game kernel: the workgroup that finishes last
+// folds the records of all workgroups, merges the launch's best into the running best and
+// reports a new running best (its row, value and best responses).  run == nullptr: no grid stage.
+struct FinishArgs {
+    int first;               // != 0: the running best is replaced, not merged
+    RunningBest *run;        // device
+    RunningBest *run_host;   // device-visible pinned host memory
+    float *best_x;           // [m] row of the running best
+    float *win_v;            // value of the running best (pinned host)
+    int32_t *win_br;         // [K] its best responses (pinned host)
+    unsigned *blk_br;        // [nblocks][2] packed best responses of each workgroup's best
+    unsigned *done;          // count of finished workgroups; zero between launches
+};
+
 // One sweep launch.  Either (V_out, br_out) [evaluation mode: per-candidate outputs] or
 // (blk_v, blk_i) [sweep mode: one record per workgroup] is used.
 struct SweepArgs {
@@ -41,31 +63,11 @@ struct SweepArgs {
     int slice_stages;        // LDS stages per slice (set by the launcher)
     // Small-game kernel only, gen != 0: X is not read; row c is the flat-Dirichlet row
     // gen_first + c of the generator keyed (gen_k0, gen_k1), produced in registers with the
-    // arithmetic of the generation kernel.  x_out (evaluation mode, nullable): the rows, written out.
+    // arithmetic of the generation kernel (sweep mode only).
     int gen;
     unsigned gen_k0, gen_k1;
     long long gen_first;
-    float *x_out;
-};
-
-// Running best over chunks, in device memory.
-struct RunningBest {
-    float value;
-    int   has;               // 0 until a chunk has been merged
-    long long index;
-    unsigned long long ties; // tie evaluations of all merged chunks
-};
-
-// Grid stage of a sweep launch fused with the re-evaluation of a new running best (small-game
-// path): the records of `nblocks` workgroups are in SweepArgs::blk_v / blk_i.
-struct FinishArgs {
-    long long nblocks;
-    int first;               // != 0: the running best is replaced, not merged
-    RunningBest *run;        // device
-    RunningBest *run_host;   // device-visible pinned host memory
-    float *best_x;           // [m] row of the running best
-    float *win_v;            // value of the re-evaluated row (pinned host)
-    int32_t *win_br;         // [K] its best responses (pinned host)
+    FinishArgs fin;          // small-game kernel, sweep mode
 };
 
 // Running best of one prior of a prior batch.
@@ -100,7 +102,6 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
 bool small_supported(int m, int n, int K, int storage);
 long long small_num_blocks(long long count);
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s);
-hipError_t launch_finish_small(const GameView &g, const SweepArgs &a, const FinishArgs &f, hipStream_t s);
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes);
 

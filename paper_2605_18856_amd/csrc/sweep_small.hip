@@ -29,6 +29,87 @@ constexpr int SM_NT = 2;               // 32-candidate tiles per wavefront per i
 constexpr int SM_AT_STRIDE = 12;       // floats per leader row in LDS (8 + pad: bank spread)
 constexpr int SM_MAX_TILES = 4;
 
+// Steps 5-6 inside the sweep launch.  Every workgroup, after its record is written, counts
+// itself done; the one that counts last folds all records (greatest value, lowest index among
+// equals), merges the launch's best into the running best with a strict "greater than", and for
+// a new running best reports value, row and best responses (unpacked from the workgroup record;
+// nothing is evaluated again).  There is no waiting on other workgroups anywhere: a workgroup
+// either leaves or, being last, finds every record complete.  Visibility without cache-wide
+// fences (a device-scope release fence writes back the whole L2 of the die, and a thousand
+// workgroups issuing one multiplied the kernel's time): records, tie counts and the done count
+// are all device-scope atomic accesses, which go through to memory past the per-die caches; a
+// workgroup waits for its own to be acknowledged before it counts itself done, and the last
+// workgroup reads them with device-scope atomic loads.
+template <int TILES, bool GEN>
+__device__ __forceinline__ void grid_stage(const SweepArgs &a, unsigned block, unsigned nblocks)
+{
+    __shared__ int is_last;
+    __shared__ float gs_v[SM_WAVES];
+    __shared__ long long gs_i[SM_WAVES];
+    __shared__ unsigned gs_b[SM_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    (void)block;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's record stores and tie atomics are done
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned prev = __hip_atomic_fetch_add(a.fin.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = prev == nblocks - 1u;
+    }
+    __syncthreads();
+    if (!is_last) return;                  // whole workgroup
+    float bv = -INFINITY;
+    long long bi = LLONG_MAX;
+    unsigned bb = 0u;
+    for (unsigned b = tid; b < nblocks; b += SM_WAVES * 64) {
+        const float v = __hip_atomic_load(a.blk_v + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const long long i = __hip_atomic_load(a.blk_i + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; bb = b; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float ov = __shfl_xor(bv, d, 64);
+        const long long oi = __shfl_xor(bi, d, 64);
+        const unsigned ob = __shfl_xor(bb, d, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; bb = ob; }
+    }
+    if (lane == 0) { gs_v[wave] = bv; gs_i[wave] = bi; gs_b[wave] = bb; }
+    __syncthreads();
+    if (tid != 0) return;
+    for (int w = 1; w < SM_WAVES; ++w)
+        if (gs_v[w] > bv || (gs_v[w] == bv && gs_i[w] < bi)) { bv = gs_v[w]; bi = gs_i[w]; bb = gs_b[w]; }
+    RunningBest r = *a.fin.run;
+    if (a.fin.first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
+    const bool fresh_best = bi != LLONG_MAX && (!r.has || bv > r.value);
+    if (fresh_best) { r.value = bv; r.index = bi; r.has = 1; }
+    // every workgroup added its ties before it counted itself done; the next launch starts from zero
+    r.ties += __hip_atomic_exchange(a.tie_counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *a.fin.run = r;
+    *a.fin.run_host = r;
+    if (fresh_best) {
+        *a.fin.win_v = bv;
+        const unsigned p0 = __hip_atomic_load(a.fin.blk_br + 2 * (size_t)bb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned p1 = __hip_atomic_load(a.fin.blk_br + 2 * (size_t)bb + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int p = 0; p < 2 * TILES; ++p) {
+            const int t = 4 * (p >> 1) + (p & 1);
+            a.fin.win_br[t] = (int32_t)((p0 >> (3 * p)) & 7u);          // lane half 0: types 4T, 4T+1
+            a.fin.win_br[t + 2] = (int32_t)((p1 >> (3 * p)) & 7u);      // lane half 1: types 4T+2, 4T+3
+        }
+        const long long row = bi - a.index_base;
+        if (GEN) {
+            float q[SM_M];
+            dirichlet_quad_raw(a.gen_first + row, 0u, a.gen_k0, a.gen_k1, q[0], q[1], q[2], q[3]);
+            dirichlet_quad_raw(a.gen_first + row, 1u, a.gen_k0, a.gen_k1, q[4], q[5], q[6], q[7]);
+            const float sum = dirichlet_quad_sum(q[0], q[1], q[2], q[3]) + dirichlet_quad_sum(q[4], q[5], q[6], q[7]);
+            dirichlet_quad_scale(sum, SM_M, q[0], q[1], q[2], q[3]);
+            dirichlet_quad_scale(sum, SM_M, q[4], q[5], q[6], q[7]);
+            for (int i = 0; i < SM_M; ++i) a.fin.best_x[i] = q[i];
+        } else {
+            for (int i = 0; i < SM_M; ++i) a.fin.best_x[i] = a.X[row * SM_M + i];
+        }
+    }
+    __hip_atomic_store(a.fin.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
 // Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).  The body of a
 // workgroup; block / nblocks are its place in the (one-dimensional) grid of the pass.
@@ -39,6 +120,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     __shared__ __attribute__((aligned(16))) float at_lds[TILES * 4 * SM_N * SM_AT_STRIDE];
     __shared__ float red_v[SM_WAVES];
     __shared__ unsigned red_c[SM_WAVES];
+    __shared__ unsigned red_p[SM_WAVES][2];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -114,6 +196,9 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 
     float best_v = -INFINITY;
     unsigned best_c = 0xFFFFFFFFu;
+    // best responses of the lane's best candidate, three bits each: this lane half's types only,
+    // type 4T + 2h + tl at bits 3(2T + tl)
+    unsigned best_pk = 0u;
     unsigned tie_count = 0;
 
 #pragma unroll 1
@@ -128,10 +213,12 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         // straight-line block (four independent dependency chains for the scheduler to
         // interleave); the exact tie routine is a single rare branch at the end.
         float vhalf[SM_NT];
+        unsigned pk[SM_NT];
         bool all_ok[SM_NT];
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
             vhalf[ct] = 0.0f;
+            pk[ct] = 0u;
             all_ok[ct] = (task * per_iter + ct * 32 + 32) <= count;            // wave-uniform
         }
 #pragma unroll
@@ -213,6 +300,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl) {
                     vhalf[ct] = fmaf(prior[T][tl], l[ct][tl], vhalf[ct]);
+                    if (!EVAL) pk[ct] |= (unsigned)idx[ct][tl] << (3 * (2 * T + tl));
                     if (EVAL) {
                         const unsigned c = task * per_iter + ct * 32 + col;
                         if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx[ct][tl];
@@ -228,9 +316,8 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             if (!(v == v)) v = -INFINITY;
             if (EVAL) {
                 if (a.V_out && ok && h == 0) a.V_out[c] = v;
-                if (GEN && a.x_out && ok) *(f32x4 *)(a.x_out + (size_t)c * SM_M + 4 * h) = xo[ct];
             } else if (ok && v > best_v) {           // a lane meets its candidates in ascending order
-                best_v = v; best_c = c;
+                best_v = v; best_c = c; best_pk = pk[ct];
             }
         }
     }
@@ -240,19 +327,30 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         for (int d = 16; d >= 1; d >>= 1) {          // both lane halves hold the same values
             const float ov = __shfl_xor(best_v, d, 64);
             const unsigned oc = __shfl_xor(best_c, d, 64);
-            if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; }
+            const unsigned op = __shfl_xor(best_pk, d, 64);
+            if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; best_pk = op; }
         }
-        if (lane == 0) { red_v[wave] = best_v; red_c[wave] = best_c; }
+        // lanes 0 and 32 now hold the same candidate, each with its half of the best responses
+        if (lane == 0) { red_v[wave] = best_v; red_c[wave] = best_c; red_p[wave][0] = best_pk; }
+        if (lane == 32) red_p[wave][1] = best_pk;
         __syncthreads();
         if (tid == 0) {
+            int bw = 0;
             for (int w = 1; w < SM_WAVES; ++w)
                 if (red_v[w] > best_v || (red_v[w] == best_v && red_c[w] < best_c)) {
-                    best_v = red_v[w]; best_c = red_c[w];
+                    best_v = red_v[w]; best_c = red_c[w]; bw = w;
                 }
-            a.blk_v[block] = best_v;
-            a.blk_i[block] = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
+            const long long gi = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
+            // (device-scope stores: the workgroup that runs the grid stage may sit on another die)
+            __hip_atomic_store(a.blk_v + block, best_v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.blk_i + block, gi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.fin.blk_br) {
+                __hip_atomic_store(a.fin.blk_br + 2 * (size_t)block, red_p[bw][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.fin.blk_br + 2 * (size_t)block + 1, red_p[bw][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
+        if (a.fin.run) grid_stage<TILES, GEN>(a, block, nblocks);
     }
 }
 
@@ -269,66 +367,6 @@ __global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
 sweep_small_gen_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, false, true>(g, a, blockIdx.x, gridDim.x);
-}
-
-// Steps 5-6 for the small-game path in one single-workgroup launch: fold the workgroup records
-// of a sweep launch (greatest value, lowest index among equals), merge into the running best
-// with a strict "greater than", and, when the running best changed, keep its row and evaluate
-// it again with per-candidate outputs, which gives its K best responses (same instruction
-// sequence as the sweep, hence the same value bit for bit).
-template <int TILES, bool GEN>
-__global__ void __launch_bounds__(SM_WAVES * 64)
-small_finish_kernel(GameView g, SweepArgs a, FinishArgs f)
-{
-    __shared__ float sv[SM_WAVES];
-    __shared__ long long si[SM_WAVES];
-    __shared__ long long win;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float bv = -INFINITY;
-    long long bi = LLONG_MAX;
-    for (long long b = tid; b < f.nblocks; b += SM_WAVES * 64) {
-        const float v = a.blk_v[b];
-        const long long i = a.blk_i[b];
-        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const float ov = __shfl_xor(bv, d, 64);
-        const long long oi = __shfl_xor(bi, d, 64);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-    }
-    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
-    __syncthreads();
-    if (tid == 0) {
-        for (int w = 1; w < SM_WAVES; ++w)
-            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
-        long long w_row = -1;
-        RunningBest r = *f.run;
-        if (f.first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
-        if (bi != LLONG_MAX && (!r.has || bv > r.value)) {
-            r.value = bv; r.index = bi; r.has = 1;
-            w_row = bi - a.index_base;
-        }
-        r.ties += *a.tie_counter;
-        *a.tie_counter = 0ull;                   // the next chunk starts from zero
-        *f.run = r;
-        *f.run_host = r;
-        win = w_row;
-    }
-    __syncthreads();
-    const long long row = win;
-    if (row < 0) return;                         // whole workgroup
-    SweepArgs e{};
-    e.count = 1; e.index_base = 0;
-    e.V_out = f.win_v; e.br_out = f.win_br;
-    if (GEN) {
-        e.gen = 1; e.gen_k0 = a.gen_k0; e.gen_k1 = a.gen_k1; e.gen_first = a.gen_first + row;
-        e.x_out = f.best_x;
-    } else {
-        if (tid < SM_M) f.best_x[tid] = a.X[row * SM_M + tid];
-        e.X = a.X + row * SM_M;
-    }
-    small_body<TILES, true, GEN>(g, e, 0u, 1u);
 }
 
 typedef void (*small_kernel_t)(GameView, SweepArgs);
@@ -350,18 +388,6 @@ small_kernel_t small_gen_kernel_for(int K)
     case 2: return sweep_small_gen_kernel<2>;
     case 3: return sweep_small_gen_kernel<3>;
     case 4: return sweep_small_gen_kernel<4>;
-    }
-    return nullptr;
-}
-
-typedef void (*small_finish_t)(GameView, SweepArgs, FinishArgs);
-small_finish_t small_finish_for(int K, bool gen)
-{
-    switch (K / 4) {
-    case 1: return gen ? small_finish_kernel<1, true> : small_finish_kernel<1, false>;
-    case 2: return gen ? small_finish_kernel<2, true> : small_finish_kernel<2, false>;
-    case 3: return gen ? small_finish_kernel<3, true> : small_finish_kernel<3, false>;
-    case 4: return gen ? small_finish_kernel<4, true> : small_finish_kernel<4, false>;
     }
     return nullptr;
 }
@@ -391,15 +417,6 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
     if (!k) return hipErrorNotSupported;
     if (!a.gen && ((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
     hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_finish_small(const GameView &g, const SweepArgs &a, const FinishArgs &f, hipStream_t s)
-{
-    if (f.nblocks <= 0) return hipSuccess;
-    small_finish_t k = small_finish_for(g.K, a.gen != 0);
-    if (!k) return hipErrorNotSupported;
-    hipLaunchKernelGGL(k, dim3(1), dim3(SM_WAVES * 64), 0, s, g, a, f);
     return hipGetLastError();
 }
 

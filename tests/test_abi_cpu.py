@@ -95,6 +95,9 @@ def test_null_handles_are_rejected():
     assert L.bsse_refine(None, 1, 1, 4, 0, 0, 0.5, 0.5, None, None, None) == bsse.BSSE_EINVAL
     assert L.bsse_solve_realised(None, None, 0, 1, None, None, None, None, None) == bsse.BSSE_EINVAL
     assert L.bsse_dirichlet_around(None, 1, 0, 4, None, 0.5, None) == bsse.BSSE_EINVAL
+    assert L.bsse_sweep_dirichlet(None, 1, 0, 4, ctypes.byref(res), None) == bsse.BSSE_EINVAL
+    assert L.bsse_sweep_dirichlet_chunk(None, 1, 0, 4, 0) == bsse.BSSE_EINVAL
+    assert L.bsse_sweep_best_row(None, None) == bsse.BSSE_EINVAL
     assert L.bsse_set_stream(None, None) == bsse.BSSE_EINVAL
     assert L.bsse_set_timing(None, 1) == bsse.BSSE_EINVAL
     L.bsse_destroy(None)

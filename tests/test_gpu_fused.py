@@ -18,15 +18,27 @@ pytestmark = pytest.mark.gpu
 
 
 def _two_step(g, seed, first, count):
+    """(outcome, winning row) of generate-then-sweep; the row as the handle reports it must be the
+    row of the buffer at best_index"""
     import torch
     X = torch.empty((max(count, 1), g.m), dtype=torch.float32, device="cuda")
     bsse.bsse_dirichlet(g, seed, first, count, X)
     out = bsse.bsse_sweep(g, X, count)
     torch.cuda.synchronize()
-    return out
+    row = X[out.best_index].cpu().numpy()
+    assert np.array_equal(bsse.bsse_sweep_best_row(g), row)
+    return out, row
+
+
+def _fused(g, seed, first, count):
+    out = bsse.bsse_sweep_dirichlet(g, seed, first, count)
+    return out, bsse.bsse_sweep_best_row(g)
 
 
 def _same(a, b):
+    if isinstance(a, tuple):
+        assert np.array_equal(a[1], b[1])             # the winning row, bit for bit
+        a, b = a[0], b[0]
     assert a.best_index == b.best_index
     assert np.float32(a.best_value) == np.float32(b.best_value)
     assert a.n_evals == b.n_evals and a.n_tie_evals == b.n_tie_evals
@@ -42,7 +54,7 @@ def test_small_game_fused_equals_two_step(K):
         for seed, first, count in [(1, 0, 1), (2, 0, 31), (3, 7, 64), (4, 12345, 65), (5, 0, 1000),
                                    (6, (1 << 32) - 100, 777), (7, 3, (1 << 17) + 5),
                                    ((1 << 63) + 12345, (1 << 40) + 1, 50000)]:
-            _same(bsse.bsse_sweep_dirichlet(g, seed, first, count), _two_step(g, seed, first, count))
+            _same(_fused(g, seed, first, count), _two_step(g, seed, first, count))
 
 
 @pytest.mark.parametrize("shape,storage", [((3, 3, 2), "f32"), ((5, 7, 3), "f32"), ((16, 16, 8), "f32"),
@@ -53,7 +65,7 @@ def test_other_shapes_equal_two_step(shape, storage):
                                 storage=storage)
     with _make(game) as g:
         for seed, first, count in [(11, 0, 1), (12, 5, 999), (13, 1 << 33, 40000)]:
-            _same(bsse.bsse_sweep_dirichlet(g, seed, first, count), _two_step(g, seed, first, count))
+            _same(_fused(g, seed, first, count), _two_step(g, seed, first, count))
 
 
 def test_staged_pieces_and_chunks():
@@ -63,7 +75,7 @@ def test_staged_pieces_and_chunks():
     count = (1 << 22) + 4097
     with _make(game) as g:
         one = bsse.bsse_sweep_dirichlet(g, 21, 10, count)
-        _same(one, _two_step(g, 21, 10, count))
+        _same((one, bsse.bsse_sweep_best_row(g)), _two_step(g, 21, 10, count))
         bsse.bsse_sweep_reset(g)
         cuts = [0, 1000, (1 << 22) - 3, count]
         for lo, hi in zip(cuts[:-1], cuts[1:]):
@@ -101,6 +113,9 @@ def test_arguments():
     with _make(game) as g:
         out = bsse.bsse_sweep_dirichlet(g, 1, 0, 0)
         assert out.best_index == -1 and out.n_evals == 0
+        with pytest.raises(bsse.BsseError) as e:
+            bsse.bsse_sweep_best_row(g)
+        assert e.value.status == bsse.BSSE_ESTATE
         for first, count in [(-1, 10), (0, -1)]:
             with pytest.raises(bsse.BsseError) as e:
                 bsse.bsse_sweep_dirichlet(g, 1, first, count)
