@@ -159,11 +159,12 @@ bsse_status bsse_sweep(bsse_game *g, const float *candidates_dev, int64_t count,
 /* The same sweep streamed in chunks (step 6, the running best over chunks):
  *   bsse_sweep_reset  forgets the running best;
  *   bsse_sweep_chunk  enqueues the sweep of one chunk whose row r has global index
- *                     index_base + r, and merges its best into the running best with a
- *                     strict "greater than", so equal values keep the lowest global
- *                     index when chunks are submitted in ascending order; it does not
- *                     wait for the device; the winning row is copied into the handle,
- *                     so the chunk buffer may be reused once the stream has passed it;
+ *                     index_base + r, and merges its best into the running best: greater
+ *                     value, then lower global index, so the result is that of one sweep
+ *                     over all chunks in index order, whatever order they are submitted
+ *                     in; it does not wait for the device; the winning row is copied into
+ *                     the handle, so the chunk buffer may be reused once the stream has
+ *                     passed it;
  *   bsse_sweep_result waits for the stream and reports like bsse_sweep. */
 bsse_status bsse_sweep_reset(bsse_game *g);
 bsse_status bsse_sweep_chunk(bsse_game *g, const float *candidates_dev, int64_t count,

@@ -88,8 +88,12 @@ struct bsse_game {
     size_t lat_table_cap = 0;
     float *blk_v = nullptr;
     long long *blk_i = nullptr;
-    unsigned *blk_br = nullptr;  // [blk_cap][2] packed best responses (small-game kernel)
-    unsigned *done = nullptr;    // finished-workgroup count of the small-game kernel's grid stage
+    // small-game kernel: per-workgroup running bests of the current sweep, folded on demand
+    SmallSlot *slots = nullptr;
+    unsigned epoch = 0;          // of the current sweep (slots of other epochs are stale)
+    bool fold_pending = false;   // chunks swept since the last fold
+    bool fold_first = true;      // the next fold is the first of its sweep
+    bool ties_dirty = false;     // the device tie counter may be non-zero
     long long blk_cap = 0;
     RunningBest *run = nullptr;
     float *best_x = nullptr;
@@ -164,7 +168,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->dB); (void)hipFree(g->dAT); (void)hipFree(g->dprior);
     (void)hipFree(g->dBpack); (void)hipFree(g->dATpack);
     (void)hipFree(g->gen); (void)hipFree(g->lat_table);
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->blk_br); (void)hipFree(g->done);
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->slots);
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
     (void)hipFree(g->win_l);
     g->pri.release();
@@ -182,11 +186,10 @@ bsse_status ensure_blocks(bsse_game *g, long long nblocks)
     if (nblocks <= g->blk_cap) return BSSE_OK;
     // the stream may still be reading the old workspace
     HIP_TRY(hipStreamSynchronize(g->stream));
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->blk_br);
-    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_br = nullptr; g->blk_cap = 0;
+    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
+    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_cap = 0;
     HIP_TRY(hipMalloc((void **)&g->blk_v, (size_t)nblocks * sizeof(float)));
     HIP_TRY(hipMalloc((void **)&g->blk_i, (size_t)nblocks * sizeof(long long)));
-    HIP_TRY(hipMalloc((void **)&g->blk_br, (size_t)nblocks * 2 * sizeof(unsigned)));
     g->blk_cap = nblocks;
     return BSSE_OK;
 }
@@ -376,7 +379,8 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->done, sizeof(unsigned))) != BSSE_OK) break;
+        if (use_mfma && mfma_is_small(variant) &&       // epoch 0 marks a slot never written
+            (st = zeroed((void **)&g->slots, (size_t)small_num_slots() * sizeof(SmallSlot))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->win_l, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
@@ -614,20 +618,32 @@ namespace {
 
 // One chunk through the sweep kernel and the merge into the running best.  a.X / a.gen*, a.count
 // and a.index_base are set by the caller; the device is current.
+bool on_small_kernel(const bsse_game *g)
+{
+    return g->path != PATH_VALU && mfma_is_small(g->view.variant);
+}
+
 bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
 {
     bsse_status st;
     const long long count = a.count;
-    const long long nblocks = sweep_blocks(g, count);
-    if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
-    a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
-    const bool small = g->path != PATH_VALU && mfma_is_small(g->view.variant);
+    const bool small = on_small_kernel(g);
+    long long nblocks = 0;
     if (small) {
-        // the grid stage, the merge and the report of a new running best run inside the launch
-        a.fin.first = g->fresh ? 1 : 0;
-        a.fin.run = g->run; a.fin.run_host = &g->h_out->run; a.fin.best_x = g->best_x;
-        a.fin.win_v = &g->h_out->fin_v; a.fin.win_br = g->h_br;
-        a.fin.blk_br = g->blk_br; a.fin.done = g->done;
+        // every workgroup keeps its own running best over the chunks: nothing but the sweep
+        // kernel runs per chunk; bsse_sweep_result folds
+        if (g->fresh) {
+            g->epoch += 1;
+            if (g->epoch == 0) g->epoch = 1;         // 0 is the mark of a slot never written
+            g->fold_first = true;
+            if (g->ties_dirty) HIP_TRY(launch_clear_u64(g->tie_counter, g->stream));   // an abandoned sweep's
+        }
+        a.small.slots = g->slots; a.small.epoch = g->epoch;
+        a.tie_counter = g->tie_counter;
+    } else {
+        nblocks = sweep_blocks(g, count);
+        if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
+        a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (g->timing) {
@@ -641,19 +657,35 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
         g->ev.push_back(e0); g->ev.push_back(e1);
     }
     HIP_TRY(le);
-    if (!small)
+    if (small) {
+        g->fold_pending = true; g->ties_dirty = true;
+    } else {
         HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, a.X, a.index_base, g->m,
                                     g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
                                     g->stream));
+    }
     g->fresh = false;
     g->n_evals += count * g->K;
     return BSSE_OK;
 }
 
-bool fuses_generation(const bsse_game *g)
+// Small-game kernel: fold the workgroups' running bests into the handle's result (value, index,
+// row, best responses, tie count).  No-op when nothing was swept since the last fold.
+bsse_status fold_small(bsse_game *g)
 {
-    return g->path != PATH_VALU && mfma_is_small(g->view.variant);
+    if (!on_small_kernel(g) || !g->fold_pending) return BSSE_OK;
+    FinishArgs f{};
+    f.slots = g->slots; f.nslots = small_num_slots(); f.epoch = g->epoch;
+    f.first = g->fold_first ? 1 : 0;
+    f.tie_counter = g->tie_counter;
+    f.run = g->run; f.run_host = &g->h_out->run; f.best_x = g->best_x;
+    f.win_v = &g->h_out->fin_v; f.win_br = g->h_br;
+    HIP_TRY(launch_finish_small(g->view, f, g->stream));
+    g->fold_pending = false; g->fold_first = false; g->ties_dirty = false;
+    return BSSE_OK;
 }
+
+bool fuses_generation(const bsse_game *g) { return on_small_kernel(g); }
 
 bsse_status check_rows(int64_t first, int64_t count)
 {
@@ -749,8 +781,11 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
         return BSSE_OK;
     }
     // best responses of the winner: the same kernel, one row, per-candidate outputs written
-    // straight into pinned host memory
-    if (!(g->path != PATH_VALU && mfma_is_small(g->view.variant))) {   // (that path has done it already)
+    // straight into pinned host memory (the small-game kernel carries them with its records)
+    if (on_small_kernel(g)) {
+        bsse_status st = fold_small(g);
+        if (st != BSSE_OK) return st;
+    } else {
         SweepArgs a{};
         a.X = g->best_x; a.count = 1; a.index_base = 0;
         a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
@@ -778,6 +813,10 @@ extern "C" bsse_status bsse_sweep_best_row(bsse_game *g, float *x_out)
     if (!x_out) return fail(BSSE_EINVAL, "x_out is NULL");
     DeviceGuard dg(g->device);
     if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    if (!g->fresh) {
+        bsse_status st = fold_small(g);
+        if (st != BSSE_OK) return st;
+    }
     HIP_TRY(hipStreamSynchronize(g->stream));
     if (g->fresh || !g->h_out->run.has) return fail(BSSE_ESTATE, "no candidate has been swept since the last reset");
     HIP_TRY(hipMemcpy(x_out, g->best_x, (size_t)g->m * sizeof(float), hipMemcpyDeviceToHost));

@@ -29,18 +29,36 @@ struct RunningBest {
     unsigned long long ties; // tie evaluations of all merged chunks
 };
 
-// Grid stage of a sweep launch inside the small-game kernel: the workgroup that finishes last
-// folds the records of all workgroups, merges the launch's best into the running best and
-// reports a new running best (its row, value and best responses).  run == nullptr: no grid stage.
+// Small-game kernel, sweep mode.  Workgroup b keeps its own running best over the chunks of a
+// sweep in slot b (read and rewritten by that workgroup alone, so chunk launches need no grid
+// stage and no synchronisation); a one-workgroup kernel folds the slots when the result is asked
+// for.  A slot belongs to the current sweep when its epoch matches.
+struct SmallSlot {
+    float value;
+    unsigned epoch;
+    long long index;         // global candidate index
+    unsigned br[2];          // packed best responses (three bits per type; one word per lane half)
+    unsigned pad[2];
+    float x[8];              // the row itself
+};
+
+struct SmallSweep {
+    SmallSlot *slots;        // [small_num_slots()]; nullptr outside the small-game sweep
+    unsigned epoch;
+};
+
+// Fold of the slots into the result of the sweep.
 struct FinishArgs {
-    int first;               // != 0: the running best is replaced, not merged
+    const SmallSlot *slots;
+    int nslots;
+    unsigned epoch;
+    int first;               // != 0: first fold of this sweep (the tie count restarts)
+    unsigned long long *tie_counter;
     RunningBest *run;        // device
     RunningBest *run_host;   // device-visible pinned host memory
-    float *best_x;           // [m] row of the running best
-    float *win_v;            // value of the running best (pinned host)
+    float *best_x;           // [m] row of the best
+    float *win_v;            // its value (pinned host)
     int32_t *win_br;         // [K] its best responses (pinned host)
-    unsigned *blk_br;        // [nblocks][2] packed best responses of each workgroup's best
-    unsigned *done;          // count of finished workgroups; zero between launches
 };
 
 // One sweep launch.  Either (V_out, br_out) [evaluation mode: per-candidate outputs] or
@@ -67,7 +85,7 @@ struct SweepArgs {
     int gen;
     unsigned gen_k0, gen_k1;
     long long gen_first;
-    FinishArgs fin;          // small-game kernel, sweep mode
+    SmallSweep small;        // small-game kernel, sweep mode
 };
 
 // Running best of one prior of a prior batch.
@@ -102,6 +120,8 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
 bool small_supported(int m, int n, int K, int storage);
 long long small_num_blocks(long long count);
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s);
+int small_num_slots();
+hipError_t launch_finish_small(const GameView &g, const FinishArgs &f, hipStream_t s);
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes);
 
@@ -112,6 +132,9 @@ hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long 
                                const float *X, long long index_base, int m, int first,
                                unsigned long long *tie_counter, RunningBest *run,
                                RunningBest *run_host, float *best_x, hipStream_t s);
+
+// *p = 0 by a one-thread kernel (a fill node that is safe to capture in a graph).
+hipError_t launch_clear_u64(unsigned long long *p, hipStream_t s);
 
 // Prior batch (see prior_batch.hip): V_p[c] = sum_t priors[p][t] * L[c][t] and the arg-max over c
 // for each of P priors, merged into run[P] (first != 0: replaced).  blk_v / blk_i: workspace of

@@ -121,7 +121,7 @@ prior_batch_kernel(const float *__restrict__ L, long long count, long long index
 }
 
 // One workgroup per prior folds the records of all workgroups and merges into the running best
-// of that prior with a strict "greater than" (an earlier chunk keeps the win on equal values).
+// of that prior (greater value, then lower index).
 __global__ void __launch_bounds__(256)
 prior_fold_kernel(const float *__restrict__ blk_v, const long long *__restrict__ blk_i, int nblocks,
                   int P, int first, PriorBest *__restrict__ run)
@@ -149,7 +149,9 @@ prior_fold_kernel(const float *__restrict__ blk_v, const long long *__restrict__
             if (pb_better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
         PriorBest r = run[p];
         if (first) { r.value = 0.0f; r.has = 0; r.index = -1; }
-        if (bi != LLONG_MAX && (!r.has || bv > r.value)) { r.value = bv; r.index = bi; r.has = 1; }
+        if (bi != LLONG_MAX && (!r.has || bv > r.value || (bv == r.value && bi < r.index))) {
+            r.value = bv; r.index = bi; r.has = 1;
+        }
         run[p] = r;
     }
 }

@@ -1,8 +1,8 @@
 // Step 5/6: grid stage of the arg-max over candidates, and the merge into the running best
 // over chunks.  The sweep kernels leave one (value, global index) record per workgroup; one
 // workgroup here folds them (greatest value, lowest index among equals; no float atomics, so
-// the result does not depend on scheduling) and merges with a strict "greater than", so that
-// an earlier chunk keeps the win on equal values.  When the running best changes, the
+// the result does not depend on scheduling) and merges by the same rule (greater value, then
+// lower global index), so the result does not depend on the order of the chunks either.  When the running best changes, the
 // winning candidate row is copied into the handle so the chunk buffer can be recycled.
 #include "bsse_internal.h"
 #include <limits.h>
@@ -50,7 +50,7 @@ reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict
         long long w_row = -1;
         RunningBest r = *run;
         if (first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
-        if (bi != LLONG_MAX && (!r.has || bv > r.value)) {
+        if (bi != LLONG_MAX && (!r.has || bv > r.value || (bv == r.value && bi < r.index))) {
             r.value = bv;
             r.index = bi;
             r.has = 1;
@@ -68,7 +68,15 @@ reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict
         for (int i = threadIdx.x; i < m; i += RT) best_x[i] = X[row * m + i];
 }
 
+__global__ void clear_u64_kernel(unsigned long long *p) { *p = 0ull; }
+
 }  // namespace
+
+hipError_t launch_clear_u64(unsigned long long *p, hipStream_t s)
+{
+    hipLaunchKernelGGL(clear_u64_kernel, dim3(1), dim3(1), 0, s, p);
+    return hipGetLastError();
+}
 
 hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long long nblocks,
                                const float *X, long long index_base, int m, int first,

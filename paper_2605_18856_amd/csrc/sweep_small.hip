@@ -29,87 +29,6 @@ constexpr int SM_NT = 2;               // 32-candidate tiles per wavefront per i
 constexpr int SM_AT_STRIDE = 12;       // floats per leader row in LDS (8 + pad: bank spread)
 constexpr int SM_MAX_TILES = 4;
 
-// Steps 5-6 inside the sweep launch.  Every workgroup, after its record is written, counts
-// itself done; the one that counts last folds all records (greatest value, lowest index among
-// equals), merges the launch's best into the running best with a strict "greater than", and for
-// a new running best reports value, row and best responses (unpacked from the workgroup record;
-// nothing is evaluated again).  There is no waiting on other workgroups anywhere: a workgroup
-// either leaves or, being last, finds every record complete.  Visibility without cache-wide
-// fences (a device-scope release fence writes back the whole L2 of the die, and a thousand
-// workgroups issuing one multiplied the kernel's time): records, tie counts and the done count
-// are all device-scope atomic accesses, which go through to memory past the per-die caches; a
-// workgroup waits for its own to be acknowledged before it counts itself done, and the last
-// workgroup reads them with device-scope atomic loads.
-template <int TILES, bool GEN>
-__device__ __forceinline__ void grid_stage(const SweepArgs &a, unsigned block, unsigned nblocks)
-{
-    __shared__ int is_last;
-    __shared__ float gs_v[SM_WAVES];
-    __shared__ long long gs_i[SM_WAVES];
-    __shared__ unsigned gs_b[SM_WAVES];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    (void)block;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's record stores and tie atomics are done
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned prev = __hip_atomic_fetch_add(a.fin.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = prev == nblocks - 1u;
-    }
-    __syncthreads();
-    if (!is_last) return;                  // whole workgroup
-    float bv = -INFINITY;
-    long long bi = LLONG_MAX;
-    unsigned bb = 0u;
-    for (unsigned b = tid; b < nblocks; b += SM_WAVES * 64) {
-        const float v = __hip_atomic_load(a.blk_v + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const long long i = __hip_atomic_load(a.blk_i + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; bb = b; }
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const float ov = __shfl_xor(bv, d, 64);
-        const long long oi = __shfl_xor(bi, d, 64);
-        const unsigned ob = __shfl_xor(bb, d, 64);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; bb = ob; }
-    }
-    if (lane == 0) { gs_v[wave] = bv; gs_i[wave] = bi; gs_b[wave] = bb; }
-    __syncthreads();
-    if (tid != 0) return;
-    for (int w = 1; w < SM_WAVES; ++w)
-        if (gs_v[w] > bv || (gs_v[w] == bv && gs_i[w] < bi)) { bv = gs_v[w]; bi = gs_i[w]; bb = gs_b[w]; }
-    RunningBest r = *a.fin.run;
-    if (a.fin.first) { r.value = 0.0f; r.has = 0; r.index = -1; r.ties = 0ull; }
-    const bool fresh_best = bi != LLONG_MAX && (!r.has || bv > r.value);
-    if (fresh_best) { r.value = bv; r.index = bi; r.has = 1; }
-    // every workgroup added its ties before it counted itself done; the next launch starts from zero
-    r.ties += __hip_atomic_exchange(a.tie_counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *a.fin.run = r;
-    *a.fin.run_host = r;
-    if (fresh_best) {
-        *a.fin.win_v = bv;
-        const unsigned p0 = __hip_atomic_load(a.fin.blk_br + 2 * (size_t)bb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned p1 = __hip_atomic_load(a.fin.blk_br + 2 * (size_t)bb + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int p = 0; p < 2 * TILES; ++p) {
-            const int t = 4 * (p >> 1) + (p & 1);
-            a.fin.win_br[t] = (int32_t)((p0 >> (3 * p)) & 7u);          // lane half 0: types 4T, 4T+1
-            a.fin.win_br[t + 2] = (int32_t)((p1 >> (3 * p)) & 7u);      // lane half 1: types 4T+2, 4T+3
-        }
-        const long long row = bi - a.index_base;
-        if (GEN) {
-            float q[SM_M];
-            dirichlet_quad_raw(a.gen_first + row, 0u, a.gen_k0, a.gen_k1, q[0], q[1], q[2], q[3]);
-            dirichlet_quad_raw(a.gen_first + row, 1u, a.gen_k0, a.gen_k1, q[4], q[5], q[6], q[7]);
-            const float sum = dirichlet_quad_sum(q[0], q[1], q[2], q[3]) + dirichlet_quad_sum(q[4], q[5], q[6], q[7]);
-            dirichlet_quad_scale(sum, SM_M, q[0], q[1], q[2], q[3]);
-            dirichlet_quad_scale(sum, SM_M, q[4], q[5], q[6], q[7]);
-            for (int i = 0; i < SM_M; ++i) a.fin.best_x[i] = q[i];
-        } else {
-            for (int i = 0; i < SM_M; ++i) a.fin.best_x[i] = a.X[row * SM_M + i];
-        }
-    }
-    __hip_atomic_store(a.fin.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
 // Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).  The body of a
 // workgroup; block / nblocks are its place in the (one-dimensional) grid of the pass.
@@ -340,17 +259,33 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                 if (red_v[w] > best_v || (red_v[w] == best_v && red_c[w] < best_c)) {
                     best_v = red_v[w]; best_c = red_c[w]; bw = w;
                 }
-            const long long gi = best_c == 0xFFFFFFFFu ? LLONG_MAX : a.index_base + (long long)best_c;
-            // (device-scope stores: the workgroup that runs the grid stage may sit on another die)
-            __hip_atomic_store(a.blk_v + block, best_v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(a.blk_i + block, gi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (a.fin.blk_br) {
-                __hip_atomic_store(a.fin.blk_br + 2 * (size_t)block, red_p[bw][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.fin.blk_br + 2 * (size_t)block + 1, red_p[bw][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // step 6: the workgroup's own running best over the chunks of this sweep (greater
+            // value, then lower global index); nobody else touches the slot
+            SmallSlot *slot = a.small.slots + block;
+            const long long gi = a.index_base + (long long)best_c;
+            if (best_c != 0xFFFFFFFFu &&
+                (slot->epoch != a.small.epoch || best_v > slot->value ||
+                 (best_v == slot->value && gi < slot->index))) {
+                slot->value = best_v; slot->epoch = a.small.epoch; slot->index = gi;
+                slot->br[0] = red_p[bw][0]; slot->br[1] = red_p[bw][1];
+                if (GEN) {
+                    float q[SM_M];
+                    const long long row = a.gen_first + (long long)best_c;
+                    dirichlet_quad_raw(row, 0u, a.gen_k0, a.gen_k1, q[0], q[1], q[2], q[3]);
+                    dirichlet_quad_raw(row, 1u, a.gen_k0, a.gen_k1, q[4], q[5], q[6], q[7]);
+                    const float sum = dirichlet_quad_sum(q[0], q[1], q[2], q[3]) + dirichlet_quad_sum(q[4], q[5], q[6], q[7]);
+                    dirichlet_quad_scale(sum, SM_M, q[0], q[1], q[2], q[3]);
+                    dirichlet_quad_scale(sum, SM_M, q[4], q[5], q[6], q[7]);
+#pragma unroll
+                    for (int i = 0; i < SM_M; ++i) slot->x[i] = q[i];
+                } else {
+                    const f32x4 *src = (const f32x4 *)(a.X + (size_t)best_c * SM_M);
+                    *(f32x4 *)(slot->x) = src[0];
+                    *(f32x4 *)(slot->x + 4) = src[1];
+                }
             }
         }
         if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
-        if (a.fin.run) grid_stage<TILES, GEN>(a, block, nblocks);
     }
 }
 
@@ -367,6 +302,57 @@ __global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
 sweep_small_gen_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, false, true>(g, a, blockIdx.x, gridDim.x);
+}
+
+// Steps 5-6 at the end of a sweep: fold the slots of the current sweep (greatest value, lowest
+// index among equals) and report the winner: value, index, tie count, row and best responses
+// (unpacked from the slot; nothing is evaluated again).
+__global__ void __launch_bounds__(SM_WAVES * 64)
+small_finish_kernel(int K, FinishArgs f)
+{
+    __shared__ float sv[SM_WAVES];
+    __shared__ long long si[SM_WAVES];
+    __shared__ int sb[SM_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float bv = -INFINITY;
+    long long bi = LLONG_MAX;
+    int bb = -1;
+    for (int b = tid; b < f.nslots; b += SM_WAVES * 64) {
+        if (f.slots[b].epoch != f.epoch) continue;
+        const float v = f.slots[b].value;
+        const long long i = f.slots[b].index;
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; bb = b; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float ov = __shfl_xor(bv, d, 64);
+        const long long oi = __shfl_xor(bi, d, 64);
+        const int ob = __shfl_xor(bb, d, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; bb = ob; }
+    }
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; sb[wave] = bb; }
+    __syncthreads();
+    if (tid != 0) return;
+    for (int w = 1; w < SM_WAVES; ++w)
+        if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; bb = sb[w]; }
+    RunningBest r = *f.run;
+    if (f.first) r.ties = 0ull;
+    r.ties += *f.tie_counter;
+    *f.tie_counter = 0ull;                       // counted; later chunks of the sweep add to zero
+    r.has = bb >= 0 ? 1 : 0;
+    r.value = bb >= 0 ? bv : 0.0f;
+    r.index = bb >= 0 ? bi : -1;
+    *f.run = r;
+    *f.run_host = r;
+    if (bb < 0) return;
+    *f.win_v = bv;
+    const unsigned p0 = f.slots[bb].br[0], p1 = f.slots[bb].br[1];
+    for (int p = 0; 2 * p < K; ++p) {
+        const int t = 4 * (p >> 1) + (p & 1);
+        f.win_br[t] = (int32_t)((p0 >> (3 * p)) & 7u);          // lane half 0: types 4T, 4T+1
+        f.win_br[t + 2] = (int32_t)((p1 >> (3 * p)) & 7u);      // lane half 1: types 4T+2, 4T+3
+    }
+    for (int i = 0; i < SM_M; ++i) f.best_x[i] = f.slots[bb].x[i];
 }
 
 typedef void (*small_kernel_t)(GameView, SweepArgs);
@@ -411,12 +397,20 @@ long long small_num_blocks(long long count)
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s)
 {
     if (a.count <= 0) return hipSuccess;
-    const bool eval = a.blk_v == nullptr;
+    const bool eval = a.small.slots == nullptr;
     if (a.gen && eval) return hipErrorNotSupported;      // generated rows are swept, not listed
     small_kernel_t k = a.gen ? small_gen_kernel_for(g.K) : small_kernel_for(g.K, eval);
     if (!k) return hipErrorNotSupported;
     if (!a.gen && ((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
     hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
+    return hipGetLastError();
+}
+
+int small_num_slots() { return 256 * 4; }          // the cap of small_num_blocks
+
+hipError_t launch_finish_small(const GameView &g, const FinishArgs &f, hipStream_t s)
+{
+    hipLaunchKernelGGL(small_finish_kernel, dim3(1), dim3(SM_WAVES * 64), 0, s, g.K, f);
     return hipGetLastError();
 }
 

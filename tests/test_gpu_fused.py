@@ -90,6 +90,53 @@ def test_staged_pieces_and_chunks():
         _same(bsse.bsse_sweep_result(g), one)
 
 
+@pytest.mark.parametrize("shape", [(8, 8, 4), (8, 8, 16), (3, 3, 2), (16, 16, 8)])
+def test_chunk_order_does_not_matter_and_equal_values_keep_the_lowest_index(shape):
+    """The same rows submitted as several chunks, in any order: the result is that of one sweep in
+    index order.  Submitting one buffer twice under two index bases makes every value occur twice:
+    the copy with the lower global index must win."""
+    import torch
+    m, n, K = shape
+    game = workloads.small_game(m, n, K, seed=60 + K, kind="normal")
+    count = 50000
+    with _make(game) as g:
+        X = torch.empty((count, m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, 31, 0, count, X)
+        one = bsse.bsse_sweep(g, X, count)
+        cuts = [0, 12345, 12346, 40000, count]
+        spans = list(zip(cuts[:-1], cuts[1:]))
+        for order in (spans, spans[::-1], [spans[2], spans[0], spans[3], spans[1]]):
+            bsse.bsse_sweep_reset(g)
+            for lo, hi in order:
+                bsse.bsse_sweep_chunk(g, X[lo:hi], hi - lo, lo)
+            _same(bsse.bsse_sweep_result(g), one)
+            bsse.bsse_sweep_reset(g)
+            for lo, hi in order:
+                bsse.bsse_sweep_dirichlet_chunk(g, 31, lo, hi - lo, lo)
+            _same(bsse.bsse_sweep_result(g), one)
+        for bases in ((0, count), (count, 0)):
+            bsse.bsse_sweep_reset(g)
+            for b in bases:
+                bsse.bsse_sweep_chunk(g, X, count, b)
+            twice = bsse.bsse_sweep_result(g)
+            assert twice.best_index == one.best_index
+            assert np.float32(twice.best_value) == np.float32(one.best_value)
+            assert twice.n_evals == 2 * one.n_evals and twice.n_tie_evals == 2 * one.n_tie_evals
+        # a result asked for in the middle of a sweep does not disturb it
+        bsse.bsse_sweep_reset(g)
+        bsse.bsse_sweep_chunk(g, X[:30000], 30000, 0)
+        part = bsse.bsse_sweep_result(g)
+        assert part.best_index < 30000
+        bsse.bsse_sweep_chunk(g, X[30000:], count - 30000, 30000)
+        _same(bsse.bsse_sweep_result(g), one)
+        # an abandoned sweep leaves nothing behind
+        bsse.bsse_sweep_reset(g)
+        bsse.bsse_sweep_chunk(g, X[:777], 777, 10 ** 9)
+        bsse.bsse_sweep_reset(g)
+        bsse.bsse_sweep_chunk(g, X, count, 0)
+        _same(bsse.bsse_sweep_result(g), one)
+
+
 @pytest.mark.parametrize("cfg,count", [(2, 200000), (1, 30000)])
 def test_against_the_oracle_on_its_own_rows(cfg, count):
     game = workloads.game(cfg)
