@@ -32,7 +32,7 @@ EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0}
 # (profiles/*_traffic.md; FETCH_SIZE reads half of a known-size copy on this part, so it is
 # scaled by 2.0; WRITE_SIZE reads a known-size fill exactly)
 TRAFFIC_BYTES = {
-    "config2": (16449.4 * 2.0 + 64.0) * 1024.0,
+    "config2": (144.9 * 2.0 + 49.2) * 1024.0,          # rows generated in registers: slots and payoffs only
     "config3": (1070309.2 * 2.0 + 2057.8) * 1024.0,
     "config4_chunk": (776547.9 * 2.0 + 1043.6) * 1024.0,
     "config5_sub": (1266373.4 * 2.0 + 74.5) * 1024.0,

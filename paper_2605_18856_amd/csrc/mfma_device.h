@@ -44,11 +44,12 @@ __device__ __forceinline__ int pair_min(int v)
     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
     return min((int)r[0], (int)r[1]);
 }
-// The partner lane's value (h = lane / 32 of the caller).
-__device__ __forceinline__ float pair_other(float v, int h)
+// The partner lane's value, through the LDS crossbar (no LDS memory is touched): this keeps
+// the exchange off the vector ALU, where a swap costs two copies, the swap and a select.
+// partner_addr = 4 * (lane ^ 32).
+__device__ __forceinline__ float pair_other(float v, int partner_addr)
 {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(h ? r[0] : r[1]);
+    return __uint_as_float((unsigned)__builtin_amdgcn_ds_bpermute(partner_addr, (int)__float_as_uint(v)));
 }
 __device__ __forceinline__ float pair_sum(float v)
 {

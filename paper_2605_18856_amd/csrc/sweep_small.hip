@@ -69,6 +69,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     // GEN: the rows are made here instead.  Lane half h produces components 4h..4h+3 of its
     // candidate (the thread (row, b = h) of the generation kernel); the row sum and the other four
     // components come from the partner lane.
+    const int partner_addr = 4 * (lane ^ 32);
     auto gen_task = [&](unsigned task) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
@@ -80,7 +81,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             const bool ok = c < count;
             own[ct] = ok ? f32x4{ g0, g1, g2, g3 } : f32x4{ 0, 0, 0, 0 };
 #pragma unroll
-            for (int k = 0; k < 4; ++k) oth[ct][k] = pair_other(own[ct][k], h);
+            for (int k = 0; k < 4; ++k) oth[ct][k] = pair_other(own[ct][k], partner_addr);
         }
     };
     if (!GEN && task0 < n_tasks) load_task(task0);      // first rows in flight during set-up
