@@ -155,6 +155,32 @@ def test_against_the_oracle_on_its_own_rows(cfg, count):
         assert np.array_equal(out.best_response, ref.best_br)
 
 
+def test_config2_at_bench_size_streamed_against_the_oracle():
+    """The launch configuration bench.py times: config 2, chunks of 2^20 rows generated inside the
+    sweep kernel, streamed (three chunks here), one result at the end.  The oracle generates and
+    sweeps the same 3 * 2^20 rows itself."""
+    game = workloads.game(2)
+    count, chunks = 1 << 20, 3
+    seed = game.candidate_seed
+    Xo = odir.rows(seed, 0, chunks * count, game.m).astype(np.float32)
+    ref = osweep.sweep(game.A, game.B, game.prior, Xo, nthreads=8)
+    with _make(game) as g:
+        bsse.bsse_sweep_reset(g)
+        for k in range(chunks):
+            bsse.bsse_sweep_dirichlet_chunk(g, seed, k * count, count, k * count)
+        out = bsse.bsse_sweep_result(g)
+        row = bsse.bsse_sweep_best_row(g)
+    assert out.n_evals == chunks * count * game.K
+    # the row the handle reports is the generator's row at the winning index (fp32 rounding apart)
+    assert np.allclose(row, Xo[out.best_index], rtol=4e-6, atol=1e-9)
+    v_ref, sc = osweep.value_under_profile(game.A, game.prior, Xo[out.best_index].astype(np.float64),
+                                           out.best_response)
+    assert abs(out.best_value - v_ref) <= 2 * parity.TOL_F32 * max(sc, 1e-30)
+    assert ref.values[out.best_index] >= ref.best_value - 2 * parity.TOL_F32 * max(sc, 1e-30)
+    assert out.best_index == ref.best_index            # the top two values are far apart here
+    assert np.array_equal(out.best_response, ref.best_br)
+
+
 def test_arguments():
     game = workloads.game(2)
     with _make(game) as g:
