@@ -281,6 +281,49 @@ def prior_batch_leg(P=101, steps=20):
             "speedup_over_one_sweep_per_prior": P * ms_sweep / ms_batch}
 
 
+def refinement_leg(steps=10):
+    """Survivors, local refinement and the LP polish (not part of `value`) on the config-2 game
+    and its 2^20-candidate batch: wall time per call of bsse_sweep_topk (k = 64), bsse_refine
+    (8 centres, 3 rounds of 4096-point clouds) and bsse_polish, and the values they reach."""
+    import torch
+    from paper_2605_18856_amd import bsse, workloads
+
+    game = workloads.game(2)
+    count = 1 << 20
+    g = bsse.bsse_create(game.m, game.n, game.K, game.A, game.B, game.prior)
+    bsse.bsse_dirichlet(g, game.candidate_seed, 0, count, None)        # the handle-owned set
+    sweep = bsse.bsse_sweep(g)
+    bsse.bsse_sweep_topk(g, 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        vals, idx, _ = bsse.bsse_sweep_topk(g, 64)
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        bsse.bsse_sweep(g)
+        pol = bsse.bsse_polish(g)
+    t2 = time.perf_counter()
+    ms_sweep_polish = (t2 - t1) * 1e3 / steps
+    t3 = time.perf_counter()
+    for _ in range(steps):
+        bsse.bsse_sweep(g)
+    ms_sweep = (time.perf_counter() - t3) * 1e3 / steps
+    t4 = time.perf_counter()
+    for _ in range(steps):
+        # (the refinement leaves its last local set in the handle: start from the batch again)
+        bsse.bsse_dirichlet(g, game.candidate_seed, 0, count, None)
+        _, ref_v, _, ref_evals = bsse.bsse_refine(g, 8, 3, cloud_count=4096, seed=7, radius=0.25, shrink=0.25)
+    ms_refine = (time.perf_counter() - t4) * 1e3 / steps
+    g.close()
+    return {"workload": "config2 game, 2^20 candidates (handle-owned set)",
+            "sweep_value": sweep.best_value,
+            "topk": {"k": 64, "ms_per_call": (t1 - t0) * 1e3 / steps, "kth_value": float(vals[-1])},
+            "polish": {"ms_per_call": max(ms_sweep_polish - ms_sweep, 0.0), "value": pol.value,
+                       "lp_value": pol.lp_value},
+            "refine": {"centres": 8, "rounds": 3, "cloud": 4096, "ms_per_call_with_regeneration": ms_refine,
+                       "value": ref_v, "evals": int(ref_evals)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -352,6 +395,7 @@ def main():
         line["other_workloads"] = others
         line["large_batch_sweep_kernel"] = large_batch_leg()
         line["prior_batch"] = prior_batch_leg()
+        line["refinement"] = refinement_leg()
     print(json.dumps(line), flush=True)
 
 
