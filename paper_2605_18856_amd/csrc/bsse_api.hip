@@ -66,8 +66,11 @@ struct PriorScratch {
     unsigned long long *ties = nullptr;
     size_t cap_L = 0, cap_priors = 0, cap_blk_v = 0, cap_rows = 0, cap_blk_i = 0, cap_run = 0,
            cap_br = 0, cap_ties = 0;
+    unsigned char *host = nullptr;   // pinned staging: priors on the way in, results on the way out
+    size_t cap_host = 0;
     void release()
     {
+        if (host) (void)hipHostFree(host);
         (void)hipFree(L); (void)hipFree(priors); (void)hipFree(blk_v); (void)hipFree(rows);
         (void)hipFree(blk_i); (void)hipFree(run); (void)hipFree(br); (void)hipFree(ties);
     }
@@ -912,9 +915,22 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
     if ((st = grow((void **)&w.rows, &w.cap_rows, (size_t)P * m * sizeof(float))) != BSSE_OK) return st;
     if ((st = grow((void **)&w.br, &w.cap_br, (size_t)P * K * sizeof(int32_t))) != BSSE_OK) return st;
     if ((st = grow((void **)&w.ties, &w.cap_ties, sizeof(unsigned long long))) != BSSE_OK) return st;
-    HIP_TRY(hipMemcpyAsync(w.priors, priors, (size_t)P * K * sizeof(float), hipMemcpyHostToDevice, g->stream));
-    HIP_TRY(hipMemsetAsync(w.ties, 0, sizeof(unsigned long long), g->stream));   // a counter of its own
-    HIP_TRY(hipStreamSynchronize(g->stream));          // the host array is the caller's again
+    // pinned staging, so that the copies below are asynchronous and the call waits once, at the end
+    const size_t in_bytes = (size_t)P * K * sizeof(float);
+    const size_t off_run = 0, off_br = (size_t)P * sizeof(PriorBest), off_ties = off_br + (size_t)P * K * sizeof(int32_t);
+    const size_t out_bytes = off_ties + sizeof(unsigned long long);
+    const size_t host_bytes = in_bytes > out_bytes ? in_bytes : out_bytes;
+    if (host_bytes > w.cap_host) {
+        HIP_TRY(hipStreamSynchronize(g->stream));
+        if (w.host) (void)hipHostFree(w.host);
+        w.host = nullptr; w.cap_host = 0;
+        if (hipHostMalloc((void **)&w.host, host_bytes, hipHostMallocDefault) != hipSuccess)
+            return fail(BSSE_ENOMEM, "hipHostMalloc of %zu bytes failed", host_bytes);
+        w.cap_host = host_bytes;
+    }
+    memcpy(w.host, priors, in_bytes);
+    HIP_TRY(hipMemcpyAsync(w.priors, w.host, in_bytes, hipMemcpyHostToDevice, g->stream));
+    HIP_TRY(launch_clear_u64(w.ties, g->stream));                // a counter of its own
     for (long long base = 0; base < count; base += chunk) {
         const long long rows = count - base < chunk ? count - base : chunk;
         SweepArgs a{};
@@ -924,8 +940,6 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
         HIP_TRY(launch_prior_batch(w.L, rows, base, K, w.priors, P, base == 0 ? 1 : 0, w.blk_v, w.blk_i,
                                    w.run, g->stream));
     }
-    unsigned long long ties = 0;
-    HIP_TRY(hipMemcpyAsync(&ties, w.ties, sizeof(ties), hipMemcpyDeviceToHost, g->stream));
     // best responses of the P winners: their rows, evaluated once more with per-candidate outputs
     HIP_TRY(launch_gather_rows(candidates_dev, w.run, P, m, w.rows, g->stream));
     {
@@ -933,19 +947,21 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
         a.X = w.rows; a.count = P; a.index_base = 0; a.br_out = w.br;
         HIP_TRY(launch_sweep(g, a, true));
     }
-    std::vector<PriorBest> run((size_t)P);
-    std::vector<int32_t> br(best_response_out ? (size_t)P * K : 0);
-    HIP_TRY(hipMemcpyAsync(run.data(), w.run, (size_t)P * sizeof(PriorBest), hipMemcpyDeviceToHost, g->stream));
-    if (best_response_out)
-        HIP_TRY(hipMemcpyAsync(br.data(), w.br, (size_t)P * K * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    // (the staging buffer is free again once the copy of the priors has run: same stream)
+    HIP_TRY(hipMemcpyAsync(w.host + off_run, w.run, (size_t)P * sizeof(PriorBest), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(w.host + off_br, w.br, (size_t)P * K * sizeof(int32_t), hipMemcpyDeviceToHost, g->stream));
+    HIP_TRY(hipMemcpyAsync(w.host + off_ties, w.ties, sizeof(unsigned long long), hipMemcpyDeviceToHost, g->stream));
     HIP_TRY(hipStreamSynchronize(g->stream));
+    const PriorBest *run = reinterpret_cast<const PriorBest *>(w.host + off_run);
+    unsigned long long ties = 0;
+    memcpy(&ties, w.host + off_ties, sizeof(ties));
     for (int p = 0; p < P; ++p) {
         res[p].best_value = run[p].has ? (double)run[p].value : 0.0;
         res[p].best_index = run[p].has ? (int64_t)run[p].index : -1;
         res[p].n_evals = (int64_t)count * K;
         res[p].n_tie_evals = (int64_t)ties;
     }
-    if (best_response_out) memcpy(best_response_out, br.data(), br.size() * sizeof(int32_t));
+    if (best_response_out) memcpy(best_response_out, w.host + off_br, (size_t)P * K * sizeof(int32_t));
     return BSSE_OK;
 }
 

@@ -7,7 +7,8 @@
 // and an arg-max over c (greatest value, lowest index).  Here priors sit on the lanes: lane
 // (p, s) carries prior p of the current group of up to 64 priors and candidate stream s, keeps a
 // running best over its candidates, and the streams, wavefronts and workgroups are folded at the
-// end, so the per-candidate cost is K multiply-adds per 64 priors.
+// end, so the per-candidate cost is K multiply-adds per 64 priors.  The rows of L reach the
+// lanes through LDS (coalesced copy of a tile, then broadcast reads).
 #include "bsse_internal.h"
 #include <limits.h>
 
@@ -26,10 +27,10 @@ __device__ __forceinline__ bool pb_better(float v, long long i, float bv, long l
 // [t][64]; otherwise they are read from global memory.
 __global__ void __launch_bounds__(PB_WAVES * 64)
 prior_batch_kernel(const float *__restrict__ L, long long count, long long index_base, int K,
-                   const float *__restrict__ priors, int P, int log2_pp, int pri_lds,
+                   const float *__restrict__ priors, int P, int log2_pp, int pri_lds, int tile_rows,
                    float *__restrict__ blk_v, long long *__restrict__ blk_i)
 {
-    extern __shared__ float pri[];                       // [K][64] when pri_lds
+    extern __shared__ __attribute__((aligned(16))) float pri[];   // [K][64] when pri_lds, then a tile of rows
     __shared__ float sv[PB_WAVES][64];
     __shared__ long long si[PB_WAVES][64];
 
@@ -53,42 +54,78 @@ prior_batch_kernel(const float *__restrict__ L, long long count, long long index
         }
         float bv = -INFINITY;
         long long bi = LLONG_MAX;
-        const long long c_first = wave_id * streams + s;
         if (pri_lds && (K & 3) == 0) {
-            // U candidates in flight per lane: their row loads are independent, so the memory
-            // latency is paid once per batch, not once per candidate
-            constexpr int U = 8;
+            // Rows go through LDS: the workgroup copies a tile of `tile_rows` rows with coalesced
+            // 16-byte loads (every lane a different piece), and the wavefronts then read each row
+            // as a broadcast from LDS, which costs the vector unit nothing.  (Loading the row a
+            // wavefront works on straight from memory makes all 64 lanes fetch the same 16 bytes;
+            // few such loads are in flight and the kernel sat waiting for memory.)
+            float *rows = pri + K * 64;
             const int K4 = K >> 2;
-            for (long long cb = c_first; cb < count; cb += step * U) {
-                float v[U];
-                const float4 *row[U];
+            const long long ntiles = (count + tile_rows - 1) / tile_rows;
+            int bo = -1;                                 // row of the lane's best so far (count <= 2^31)
+            float q[16];                                 // the lane's prior, when K <= 16
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const long long c = cb + u * step;
-                    row[u] = reinterpret_cast<const float4 *>(L + (c < count ? c : cb) * K);
-                    v[u] = 0.0f;
+            for (int t = 0; t < 16; ++t) q[t] = t < K ? pri[t * 64 + pl] : 0.0f;
+            for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+                const long long r0 = tile * tile_rows;
+                const int nr = (int)(count - r0 < tile_rows ? count - r0 : tile_rows);
+                __syncthreads();                         // the previous tile's readers are done
+                {
+                    const float4 *src = reinterpret_cast<const float4 *>(L + r0 * K);
+                    float4 *dst = reinterpret_cast<float4 *>(rows);
+                    for (int e = tid; e < nr * K4; e += PB_WAVES * 64) dst[e] = src[e];
                 }
-                for (int t4 = 0; t4 < K4; ++t4) {
-                    float4 l[U];
+                __syncthreads();
+                // wavefront `wave`, stream s takes rows wave*streams + s, + PB_WAVES*streams, ...
+                // (a NaN value never passes "v > best", so it needs no special case here)
+                const int rstep = PB_WAVES * streams;
+                int r = wave * streams + s;
+                if (K4 <= 4) {
+                    // the lane's prior in registers; four rows per trip
+                    auto value = [&](int rr) __attribute__((always_inline)) {
+                        const float4 *row = reinterpret_cast<const float4 *>(rows + (size_t)rr * K);
+                        float v = 0.0f;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) l[u] = row[u][t4];
-                    const float q0 = pri[(4 * t4) * 64 + pl], q1 = pri[(4 * t4 + 1) * 64 + pl];
-                    const float q2 = pri[(4 * t4 + 2) * 64 + pl], q3 = pri[(4 * t4 + 3) * 64 + pl];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        v[u] = fmaf(q0, l[u].x, v[u]); v[u] = fmaf(q1, l[u].y, v[u]);
-                        v[u] = fmaf(q2, l[u].z, v[u]); v[u] = fmaf(q3, l[u].w, v[u]);
+                        for (int t4 = 0; t4 < 4; ++t4) {
+                            if (t4 >= K4) break;
+                            const float4 l = row[t4];
+                            v = fmaf(q[4 * t4], l.x, v); v = fmaf(q[4 * t4 + 1], l.y, v);
+                            v = fmaf(q[4 * t4 + 2], l.z, v); v = fmaf(q[4 * t4 + 3], l.w, v);
+                        }
+                        return v;
+                    };
+                    for (; r + 3 * rstep < nr; r += 4 * rstep) {
+                        const float v0 = value(r), v1 = value(r + rstep), v2 = value(r + 2 * rstep),
+                                    v3 = value(r + 3 * rstep);
+                        if (v0 > bv) { bv = v0; bo = (int)r0 + r; }
+                        if (v1 > bv) { bv = v1; bo = (int)r0 + r + rstep; }
+                        if (v2 > bv) { bv = v2; bo = (int)r0 + r + 2 * rstep; }
+                        if (v3 > bv) { bv = v3; bo = (int)r0 + r + 3 * rstep; }
+                    }
+                    for (; r < nr; r += rstep) {
+                        const float v = value(r);
+                        if (v > bv) { bv = v; bo = (int)r0 + r; }
+                    }
+                } else {
+                    for (; r < nr; r += rstep) {
+                        const float4 *row = reinterpret_cast<const float4 *>(rows + (size_t)r * K);
+                        float v = 0.0f;
+                        for (int t4 = 0; t4 < K4; ++t4) {
+                            const float4 l = row[t4];
+                            v = fmaf(pri[(4 * t4) * 64 + pl], l.x, v);
+                            v = fmaf(pri[(4 * t4 + 1) * 64 + pl], l.y, v);
+                            v = fmaf(pri[(4 * t4 + 2) * 64 + pl], l.z, v);
+                            v = fmaf(pri[(4 * t4 + 3) * 64 + pl], l.w, v);
+                        }
+                        if (v > bv) { bv = v; bo = (int)r0 + r; }
                     }
                 }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const long long c = cb + u * step;
-                    float x = v[u];
-                    if (!(x == x)) x = -INFINITY;
-                    if (live && c < count && x > bv) { bv = x; bi = index_base + c; }   // ascending
-                }
             }
+            if (live && bo >= 0) bi = index_base + bo;
+            if (!live) bv = -INFINITY;
         } else {
+            const long long c_first = wave_id * streams + s;
             for (long long c = c_first; c < count; c += step) {
                 const float *row = L + c * K;
                 float v = 0.0f;
@@ -187,15 +224,19 @@ hipError_t launch_prior_batch(const float *L, long long count, long long index_b
     int log2_pp = 0;
     while ((1 << log2_pp) < P && log2_pp < 6) ++log2_pp;
     const int blocks = prior_batch_blocks(count, P);
-    const size_t lds = (size_t)K * 64 * sizeof(float);
-    const int pri_lds = lds <= 96 * 1024 ? 1 : 0;
-    if (pri_lds && lds > 48 * 1024) {
+    const size_t lds_pri = (size_t)K * 64 * sizeof(float);
+    const int pri_lds = lds_pri <= 96 * 1024 ? 1 : 0;
+    // a tile of rows of about 8 KiB: small enough that the tiles outnumber the workgroups
+    int tile_rows = 2048 / K;
+    if (tile_rows < 4) tile_rows = 4;
+    const size_t lds = pri_lds ? lds_pri + (size_t)tile_rows * K * sizeof(float) : 0;
+    if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)prior_batch_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(prior_batch_kernel, dim3(blocks), dim3(PB_WAVES * 64), pri_lds ? lds : 0, s, L,
-                       count, index_base, K, priors_dev, P, log2_pp, pri_lds, blk_v, blk_i);
+    hipLaunchKernelGGL(prior_batch_kernel, dim3(blocks), dim3(PB_WAVES * 64), lds, s, L,
+                       count, index_base, K, priors_dev, P, log2_pp, pri_lds, tile_rows, blk_v, blk_i);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(prior_fold_kernel, dim3(P), dim3(256), 0, s, blk_v, blk_i, blocks, P, first, run);
