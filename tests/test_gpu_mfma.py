@@ -22,6 +22,8 @@ MFMA_SHAPES = [
     (128, 256, 2, "f32"), (100, 256, 1, "f32"),
     (16, 32, 3, "bf16"), (32, 16, 5, "bf16"), (9, 32, 2, "bf16"),
     (64, 128, 4, "bf16"), (50, 128, 2, "bf16"),
+    # whole groups of eight types: the payoff-stationary kernel of the wide bf16 game
+    (64, 128, 8, "bf16"), (64, 128, 24, "bf16"), (50, 128, 16, "bf16"),
 ]
 
 
@@ -85,7 +87,8 @@ def test_split_path_rejects_what_it_cannot_do():
 
 
 @pytest.mark.parametrize("shape", [(8, 8, 5, "f32"), (8, 8, 4, "f32"), (7, 8, 8, "f32"), (16, 16, 3, "f32"), (32, 32, 3, "f32"),
-                                   (32, 64, 2, "f32"), (16, 32, 3, "bf16"), (64, 128, 2, "bf16")],
+                                   (32, 64, 2, "f32"), (16, 32, 3, "bf16"), (64, 128, 2, "bf16"),
+                                   (64, 128, 8, "bf16"), (33, 128, 16, "bf16")],
                          ids=lambda s: "m%dn%dK%d%s" % s)
 @pytest.mark.parametrize("kind", ["dyadic", "vertex"])
 def test_mfma_exact_ties(shape, kind):
