@@ -299,7 +299,7 @@ sweep_small_kernel(GameView g, SweepArgs a)
 
 // The sweep over rows generated in registers (step 1 fused in): no candidate ever reaches memory.
 template <int TILES>
-__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 5 : TILES == 2 ? 4 : 3)
 sweep_small_gen_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, false, true>(g, a, blockIdx.x, gridDim.x);
@@ -386,14 +386,15 @@ bool small_supported(int m, int n, int K, int storage)
     return storage == 0 && n == SM_N && m == SM_M && K % 4 == 0 && K / 4 >= 1 && K / 4 <= SM_MAX_TILES;
 }
 
-// Persistent grid: one resident set of workgroups (4 per compute unit), never more than the work.
-long long small_num_blocks(long long count)
+// Persistent grid: one resident set of workgroups (per_cu per compute unit), never more than the work.
+static long long small_blocks(long long count, int per_cu)
 {
     const long long per_wg = (long long)SM_WAVES * SM_NT * 32;
     const long long need = (count + per_wg - 1) / per_wg;
-    const long long cap = 256 * 4;
+    const long long cap = 256LL * per_cu;
     return need < cap ? need : cap;
 }
+long long small_num_blocks(long long count) { return small_blocks(count, 4); }
 
 hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t s)
 {
@@ -403,11 +404,13 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
     small_kernel_t k = a.gen ? small_gen_kernel_for(g.K) : small_kernel_for(g.K, eval);
     if (!k) return hipErrorNotSupported;
     if (!a.gen && ((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
-    hipLaunchKernelGGL(k, dim3((unsigned)small_num_blocks(a.count)), dim3(SM_WAVES * 64), 0, s, g, a);
+    // (the generating kernel of a four-type game fits five workgroups per compute unit)
+    const int per_cu = a.gen && g.K == 4 ? 5 : 4;
+    hipLaunchKernelGGL(k, dim3((unsigned)small_blocks(a.count, per_cu)), dim3(SM_WAVES * 64), 0, s, g, a);
     return hipGetLastError();
 }
 
-int small_num_slots() { return 256 * 4; }          // the cap of small_num_blocks
+int small_num_slots() { return 256 * 5; }          // the largest grid launch_sweep_small uses
 
 hipError_t launch_finish_small(const GameView &g, const FinishArgs &f, hipStream_t s)
 {
