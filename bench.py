@@ -134,6 +134,7 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
         m, n, K = game.m, game.n, game.K
         gen_ops = (m / 4.0) * 60.0 + m * 10.0 + (m - 1) + 1 + m
         sweep_ops = K * (2.0 * m * n + (n - 1) + n + 2.0 * m + 2.0)
+        sweep_flops_only = flops                  # 2mn + 2m per evaluation, the figure used for the other paths
         flops = count * (gen_ops + sweep_ops)
         bytes_ = 0.0
         bound, unit, peak = "alu", "TFLOP/s", PEAK_TFLOPS["mfma_f32"]
@@ -150,6 +151,9 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
                 "kernel": ("generate + sweep (" if fused else "fused sweep (") + path + ")",
                 "kernel_ms": k_ms, "launches": launches,
                 "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": bytes_}
+    if fused:
+        # the same kernel time priced with the contraction flops alone (2mn + 2m per evaluation)
+        roofline["frac_counting_only_2mn_plus_2m_flops"] = sweep_flops_only / (k_ms * 1e-3) / 1e12 / peak
     if path in EXECUTED_FLOP_FACTOR and bound == "mfma":
         # the split path does an fp32-accurate contraction with 3 or 6 bf16 products per term:
         # frac prices the algorithmic flops against the bf16 peak; these fields give the rate the
