@@ -196,7 +196,19 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
             c1 = time.perf_counter()
             if c1 - c0 >= 12.0 or passes >= 20000 or sample < count:
                 break
+        # the same oracle on one thread, a few seconds on a prefix of the sample
+        n1 = int(max(16, min(sample, 3.0 / (per_row * max(cores, 1)) if per_row > 0 else sample)))
+        s0 = time.perf_counter()
+        p1 = 0
+        while True:
+            osweep.sweep(game.A, game.B, game.prior, Xh[:n1], per_candidate=False, nthreads=1)
+            p1 += 1
+            s1 = time.perf_counter()
+            if s1 - s0 >= 3.0 or p1 >= 20000 or n1 < sample:
+                break
+        single = p1 * n1 * game.K / (s1 - s0)
         cpu = {"value": passes * sample * game.K / (c1 - c0), "unit": "candidate-type evals/s",
+               "single_thread_value": single,
                "cores": ref.threads, "kind": "oracle",
                "sample": f"{passes} pass(es) over the first {sample} candidates of the step's "
                          f"batch of {count} ({c1 - c0:.1f} s of oracle time, fp64, OpenMP over candidates)"}
