@@ -137,6 +137,36 @@ def test_chunk_order_does_not_matter_and_equal_values_keep_the_lowest_index(shap
         _same(bsse.bsse_sweep_result(g), one)
 
 
+@pytest.mark.parametrize("shape", [(8, 8, 4), (8, 8, 12), (5, 7, 3), (32, 32, 16)])
+def test_random_chunkings_in_random_order(shape):
+    """Seeded random cuts of one batch, submitted in a random order, buffered and generated chunks
+    mixed, some sweeps abandoned: every completed sweep gives the one-shot result."""
+    import torch
+    m, n, K = shape
+    game = workloads.small_game(m, n, K, seed=70 + K, kind="normal")
+    count = 30011
+    rng = np.random.Generator(np.random.PCG64(123 + K))
+    with _make(game) as g:
+        X = torch.empty((count, m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, 41, 0, count, X)
+        one = bsse.bsse_sweep(g, X, count)
+        for trial in range(12):
+            ncuts = int(rng.integers(1, 9))
+            cuts = np.unique(np.concatenate([[0, count], rng.integers(1, count, size=ncuts)]))
+            spans = list(zip(cuts[:-1].tolist(), cuts[1:].tolist()))
+            rng.shuffle(spans)
+            bsse.bsse_sweep_reset(g)
+            for lo, hi in spans:
+                if rng.integers(0, 2):
+                    bsse.bsse_sweep_dirichlet_chunk(g, 41, lo, hi - lo, lo)
+                else:
+                    bsse.bsse_sweep_chunk(g, X[lo:hi], hi - lo, lo)
+            if trial % 4 == 3:
+                continue                                     # abandoned: the next reset starts afresh
+            _same(bsse.bsse_sweep_result(g), one)
+            assert np.array_equal(bsse.bsse_sweep_best_row(g), X[one.best_index].cpu().numpy())
+
+
 @pytest.mark.parametrize("cfg,count", [(2, 200000), (1, 30000)])
 def test_against_the_oracle_on_its_own_rows(cfg, count):
     game = workloads.game(cfg)
