@@ -127,3 +127,15 @@ def test_valid_create_without_a_device_reports_edevice():
         pytest.skip("a device is present")
     A, B, p = _tiny()
     assert _status(bsse.bsse_create, 3, 3, 2, A, B, p) == bsse.BSSE_EDEVICE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: --gpus 2 exits with a message before touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
