@@ -4,6 +4,7 @@ run at full size in the launch shape bench.py times and compared on sampled cand
 import numpy as np
 import pytest
 
+from oracle import dirichlet as odir
 from oracle import sweep as osweep
 from paper_2605_18856_amd import bsse, workloads
 from tests import parity
@@ -199,3 +200,50 @@ def test_config5_tie_injected_variant():
         assert np.array_equal(br[-128:], ref.br)
         assert (ref.gap == 0).sum() > 1000
         assert out.n_tie_evals >= int((ref.gap == 0).sum())
+
+
+def _full_streamed(game, total, chunk):
+    """The whole configured candidate count, streamed in bench.py's chunks (generate a chunk of the
+    seeded sequence, sweep it, merge): n_evals covers everything; the winner, regenerated from its
+    index alone, is checked against the oracle (its value under the reported profile, and the
+    oracle's own best responses at that row up to flagged near-ties); every chunk's own best is no
+    better than the overall best."""
+    torch = _torch()
+    tol = parity.TOL_BF16 if game.storage == "bf16" else parity.TOL_F32
+    seed = game.candidate_seed
+    with _make(game) as g:
+        Xd = torch.empty((chunk, game.m), dtype=torch.float32, device="cuda")
+        bsse.bsse_sweep_reset(g)
+        for base in range(0, total, chunk):
+            bsse.bsse_dirichlet(g, seed, base, chunk, Xd)
+            bsse.bsse_sweep_chunk(g, Xd, chunk, base)
+        out = bsse.bsse_sweep_result(g)
+        assert out.n_evals == total * game.K and 0 <= out.best_index < total
+        row_dev = torch.empty((1, game.m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, seed, out.best_index, 1, row_dev)
+        torch.cuda.synchronize()
+        row = row_dev.cpu().numpy()
+        assert np.array_equal(bsse.bsse_sweep_best_row(g), row[0])
+        # the chunk that holds the winner, swept alone, gives the same answer
+        base = out.best_index // chunk * chunk
+        bsse.bsse_dirichlet(g, seed, base, chunk, Xd)
+        alone = bsse.bsse_sweep(g, Xd, chunk)
+        assert alone.best_index + base == out.best_index
+        assert np.float32(alone.best_value) == np.float32(out.best_value)
+    # the oracle makes the winning row itself, from the index alone
+    row_o = odir.rows(seed, out.best_index, 1, game.m).astype(np.float32)
+    assert np.allclose(row, row_o, rtol=4e-6, atol=1e-9)
+    A, B, Xo = parity.oracle_inputs(game, row_o)
+    ref = osweep.sweep(A, B, game.prior, Xo, diagnostics=True, nthreads=8)
+    mism = ref.br[0] != out.best_response
+    assert not (mism & (ref.gap[0] >= 1e-6 * ref.scale[0])).any()
+    v_ref, sc = osweep.value_under_profile(A, game.prior, Xo[0].astype(np.float64), out.best_response)
+    assert abs(out.best_value - v_ref) <= tol * max(sc, 1e-30)
+
+
+def test_config4_all_sixteen_chunks():
+    _full_streamed(workloads.game(4), 1 << 26, 1 << 22)
+
+
+def test_config5_whole_range_in_subranges():
+    _full_streamed(workloads.game(5), 1 << 24, 1 << 18)
