@@ -139,6 +139,37 @@ template <int MP> struct Path<__bf16, MP> {
         const float l = l0 + l1;
         return l;
     }
+    // The same sum when the column holds three identical blocks (payoffs that are bf16 numbers,
+    // against the three parts of x): each 16 bytes of the first block are loaded once and used
+    // for all three parts, instead of gathering the same values three times.
+    template <typename BP>
+    __device__ static __forceinline__ float half_dot_rep3(const xreg *x, BP col)
+    {
+        typedef typename std::conditional<std::is_same<BP, const lds_byte *>::value,
+                                          const __attribute__((address_space(3))) u32x4 *, const u32x4 *>::type VP;
+        static_assert(XREGS % 12 == 0, "three blocks of whole 16-byte pieces");
+        constexpr int BLOCK = XREGS / 3;
+        const VP c = (VP)col;
+        float l0 = 0.0f, l1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < BLOCK; e += 4) {
+            const u32x4 v = c[e / 4];
+            const unsigned w0 = v[0], w1 = v[1], w2 = v[2], w3 = v[3];
+#pragma unroll
+            for (int term = 0; term < 3; ++term) {
+                const int b = term * BLOCK + e;
+                asm("v_dot2c_f32_bf16 %0, %2, %6\n\t"
+                    "v_dot2c_f32_bf16 %1, %3, %7\n\t"
+                    "v_dot2c_f32_bf16 %0, %4, %8\n\t"
+                    "v_dot2c_f32_bf16 %1, %5, %9\n\t"
+                    "s_nop 2"
+                    : "+v"(l0), "+v"(l1)
+                    : "v"(x[b]), "v"(x[b + 1]), "v"(x[b + 2]), "v"(x[b + 3]), "v"(w0), "v"(w1), "v"(w2), "v"(w3));
+            }
+        }
+        const float l = l0 + l1;
+        return l;
+    }
 };
 
 // ------------------------------------------------------------------------------------------
@@ -304,6 +335,12 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     for (int r = 0; r < 16; ++r)
         creg[r] = (unsigned)((N >= 32 ? acc_row_base(r) : acc_row_base(r) % N) + 4 * h) + 65536u;
 
+    // Leader-payoff half sum over a column gathered from global memory.  With three part products
+    // the column's three blocks are identical, and one is read.
+    auto leader_half = [&](const xreg *xc, const unsigned char *colp) __attribute__((always_inline)) {
+        if constexpr (TERMS == 3 && !AT_LDS) return P::half_dot_rep3(xc, colp);
+        else return P::half_dot(xc, colp);
+    };
     // Exact routine for one (candidate tile, type): recomputes the type's tiles one at a time
     // from the packed records in global memory (same instruction sequence, hence the same
     // bits), visits the exact maximisers in ascending action order, lets the leader's payoff
@@ -337,7 +374,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                         const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid32[ct];
                         if (hit == 0u) continue;                       // wave-uniform
                         const float l = pair_sum(
-                            P::half_dot(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T)));
+                            leader_half(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T)));
                         if ((hit >> col) & 1u) {
                             if (nmatch == 0 || l > lbest) { lbest = l; jbest = j; }
                             ++nmatch;
@@ -416,7 +453,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 if constexpr (AT_LDS)
                     part = P::half_dot(x[ct], at_lds + (unsigned)(((ti * N + js) * G.ats + h * HALF) * sizeof(T)));
                 else
-                    part = P::half_dot(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
+                    part = leader_half(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
                 l = pair_sum(part);
             } else {
                 exact_type(ct, group, ti, t, gmax[ct], l, js);
