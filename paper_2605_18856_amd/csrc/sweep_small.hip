@@ -389,10 +389,15 @@ bool small_supported(int m, int n, int K, int storage)
 // Persistent grid: one resident set of workgroups (per_cu per compute unit), never more than the work.
 static long long small_blocks(long long count, int per_cu)
 {
-    const long long per_wg = (long long)SM_WAVES * SM_NT * 32;
-    const long long need = (count + per_wg - 1) / per_wg;
-    const long long cap = 256LL * per_cu;
-    return need < cap ? need : cap;
+    const long long per_task = (long long)SM_NT * 32;
+    const long long n_tasks = (count + per_task - 1) / per_task;
+    const long long cap_waves = 256LL * per_cu * SM_WAVES;
+    // every wavefront walks the same number of tasks (up to one): the grid is the smallest that
+    // does the work in ceil(tasks / resident wavefronts) rounds, not the whole resident set
+    const long long rounds = (n_tasks + cap_waves - 1) / cap_waves;
+    const long long waves = rounds > 0 ? (n_tasks + rounds - 1) / rounds : 1;
+    const long long blocks = (waves + SM_WAVES - 1) / SM_WAVES;
+    return blocks < 1 ? 1 : blocks;
 }
 long long small_num_blocks(long long count) { return small_blocks(count, 4); }
 
