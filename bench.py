@@ -154,6 +154,10 @@ def run_workload(name, steps, warmup, want_cpu_baseline=True):
     if fused:
         # the same kernel time priced with the contraction flops alone (2mn + 2m per evaluation)
         roofline["frac_counting_only_2mn_plus_2m_flops"] = sweep_flops_only / (k_ms * 1e-3) / 1e12 / peak
+        # consecutive chunks run on two streams and overlap (the end of one launch with the start of
+        # the next), so a launch's own duration is longer than the step: the chip-level rate is the
+        # algorithmic work of a step over the step time
+        roofline["frac_at_step_rate"] = flops / (ms_per_step * 1e-3) / 1e12 / peak
     if path in EXECUTED_FLOP_FACTOR and bound == "mfma":
         # the split path does an fp32-accurate contraction with 3 or 6 bf16 products per term:
         # frac prices the algorithmic flops against the bf16 peak; these fields give the rate the

@@ -97,6 +97,14 @@ struct bsse_game {
     bool fold_pending = false;   // chunks swept since the last fold
     bool fold_first = true;      // the next fold is the first of its sweep
     bool ties_dirty = false;     // the device tie counter may be non-zero
+    // Chunks of generated rows need no input from the caller's stream, so after the first chunk of
+    // a sweep they alternate between two streams of the handle's own (slot sets 0 and 1; chunks on
+    // the caller's stream use set 2): the end of one launch then overlaps the start of the next.
+    // Events order them behind the caller's stream (fork) and the fold behind them (join).
+    hipStream_t aux[2] = { nullptr, nullptr };
+    hipEvent_t aux_fork = nullptr, aux_join[2] = { nullptr, nullptr };
+    bool aux_used[2] = { false, false };           // work enqueued since the last join
+    unsigned chunk_seq = 0;                        // chunks of the current sweep
     long long blk_cap = 0;
     RunningBest *run = nullptr;
     float *best_x = nullptr;
@@ -176,6 +184,11 @@ void free_game(bsse_game *g)
     (void)hipFree(g->win_l);
     g->pri.release();
     (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
+    for (int q = 0; q < 2; ++q) {
+        if (g->aux[q]) { (void)hipStreamSynchronize(g->aux[q]); (void)hipStreamDestroy(g->aux[q]); }
+        if (g->aux_join[q]) (void)hipEventDestroy(g->aux_join[q]);
+    }
+    if (g->aux_fork) (void)hipEventDestroy(g->aux_fork);
     (void)hipFree(g->centre_dev); (void)hipFree(g->stage);
     if (g->h_out) (void)hipHostFree(g->h_out);
     if (g->h_br) (void)hipHostFree(g->h_br);
@@ -214,11 +227,16 @@ bsse_status ensure_gen(bsse_game *g, unsigned long long rows)
     return BSSE_OK;
 }
 
+hipError_t launch_sweep_on(bsse_game *g, const SweepArgs &a, bool eval, hipStream_t stream)
+{
+    if (g->path == PATH_VALU) return launch_sweep_valu(g->view, a, eval, stream);
+    (void)eval;
+    return launch_sweep_mfma(g->view, a, stream);
+}
+
 hipError_t launch_sweep(bsse_game *g, const SweepArgs &a, bool eval)
 {
-    if (g->path == PATH_VALU) return launch_sweep_valu(g->view, a, eval, g->stream);
-    (void)eval;
-    return launch_sweep_mfma(g->view, a, g->stream);
+    return launch_sweep_on(g, a, eval, g->stream);
 }
 
 long long sweep_blocks(const bsse_game *g, long long count)
@@ -230,6 +248,15 @@ bsse_status take_event(bsse_game *g, hipEvent_t *e)
 {
     if (!g->ev_pool.empty()) { *e = g->ev_pool.back(); g->ev_pool.pop_back(); return BSSE_OK; }
     HIP_TRY(hipEventCreate(e));
+    return BSSE_OK;
+}
+
+// Wait for everything the handle has enqueued, on the caller's stream and on its own.
+bsse_status sync_all(bsse_game *g)
+{
+    for (int q = 0; q < 2; ++q)
+        if (g->aux[q]) { HIP_TRY(hipStreamSynchronize(g->aux[q])); g->aux_used[q] = false; }
+    HIP_TRY(hipStreamSynchronize(g->stream));
     return BSSE_OK;
 }
 
@@ -383,7 +410,7 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
         if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
         if (use_mfma && mfma_is_small(variant) &&       // epoch 0 marks a slot never written
-            (st = zeroed((void **)&g->slots, (size_t)small_num_slots() * sizeof(SmallSlot))) != BSSE_OK) break;
+            (st = zeroed((void **)&g->slots, (size_t)3 * small_num_slots() * sizeof(SmallSlot))) != BSSE_OK) break;
         if ((st = zeroed((void **)&g->win_l, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
@@ -404,7 +431,7 @@ extern "C" void bsse_destroy(bsse_game *g)
     if (!g) return;
     {
         DeviceGuard dg(g->device);
-        (void)hipStreamSynchronize(g->stream);
+        (void)sync_all(g);
     }
     free_game(g);
 }
@@ -414,7 +441,8 @@ extern "C" bsse_status bsse_set_stream(bsse_game *g, void *hip_stream)
     g_err[0] = 0;
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
     DeviceGuard dg(g->device);
-    HIP_TRY(hipStreamSynchronize(g->stream));     // earlier work keeps its order
+    bsse_status st = sync_all(g);                 // earlier work keeps its order
+    if (st != BSSE_OK) return st;
     g->stream = (hipStream_t)hip_stream;
     return BSSE_OK;
 }
@@ -626,22 +654,61 @@ bool on_small_kernel(const bsse_game *g)
     return g->path != PATH_VALU && mfma_is_small(g->view.variant);
 }
 
+// The caller's stream waits for whatever the handle's own streams still have in flight.
+bsse_status join_aux(bsse_game *g)
+{
+    for (int q = 0; q < 2; ++q) {
+        if (!g->aux_used[q]) continue;
+        HIP_TRY(hipEventRecord(g->aux_join[q], g->aux[q]));
+        HIP_TRY(hipStreamWaitEvent(g->stream, g->aux_join[q], 0));
+        g->aux_used[q] = false;
+    }
+    return BSSE_OK;
+}
+
+bsse_status ensure_aux(bsse_game *g)
+{
+    if (g->aux[0]) return BSSE_OK;
+    HIP_TRY(hipEventCreateWithFlags(&g->aux_fork, hipEventDisableTiming));
+    for (int q = 0; q < 2; ++q) {
+        HIP_TRY(hipStreamCreateWithFlags(&g->aux[q], hipStreamNonBlocking));     // default priority
+        HIP_TRY(hipEventCreateWithFlags(&g->aux_join[q], hipEventDisableTiming));
+    }
+    return BSSE_OK;
+}
+
 bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
 {
     bsse_status st;
     const long long count = a.count;
     const bool small = on_small_kernel(g);
     long long nblocks = 0;
+    hipStream_t stream = g->stream;
     if (small) {
         // every workgroup keeps its own running best over the chunks: nothing but the sweep
         // kernel runs per chunk; bsse_sweep_result folds
         if (g->fresh) {
+            if ((st = join_aux(g)) != BSSE_OK) return st;        // an abandoned sweep may still be running
             g->epoch += 1;
             if (g->epoch == 0) g->epoch = 1;         // 0 is the mark of a slot never written
             g->fold_first = true;
+            g->chunk_seq = 0;
             if (g->ties_dirty) HIP_TRY(launch_clear_u64(g->tie_counter, g->stream));   // an abandoned sweep's
         }
-        a.small.slots = g->slots; a.small.epoch = g->epoch;
+        int set = 2;                                 // the caller's stream
+        if (a.gen && g->chunk_seq > 0) {
+            // (the first chunk stays on the caller's stream, so a one-chunk sweep pays for no events)
+            if ((st = ensure_aux(g)) != BSSE_OK) return st;
+            set = (int)(g->chunk_seq & 1u);
+            if (!g->aux_used[set]) {
+                HIP_TRY(hipEventRecord(g->aux_fork, g->stream));
+                HIP_TRY(hipStreamWaitEvent(g->aux[set], g->aux_fork, 0));
+                g->aux_used[set] = true;
+            }
+            stream = g->aux[set];
+        }
+        g->chunk_seq += 1;
+        a.small.slots = g->slots + (size_t)set * small_num_slots(); a.small.epoch = g->epoch;
         a.tie_counter = g->tie_counter;
     } else {
         nblocks = sweep_blocks(g, count);
@@ -652,11 +719,11 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
     if (g->timing) {
         if ((st = take_event(g, &e0)) != BSSE_OK) return st;
         if ((st = take_event(g, &e1)) != BSSE_OK) { g->ev_pool.push_back(e0); return st; }
-        HIP_TRY(hipEventRecord(e0, g->stream));
+        HIP_TRY(hipEventRecord(e0, stream));
     }
-    hipError_t le = launch_sweep(g, a, false);
+    hipError_t le = launch_sweep_on(g, a, false, stream);
     if (g->timing) {
-        (void)hipEventRecord(e1, g->stream);
+        (void)hipEventRecord(e1, stream);
         g->ev.push_back(e0); g->ev.push_back(e1);
     }
     HIP_TRY(le);
@@ -677,8 +744,10 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
 bsse_status fold_small(bsse_game *g)
 {
     if (!on_small_kernel(g) || !g->fold_pending) return BSSE_OK;
+    bsse_status st = join_aux(g);
+    if (st != BSSE_OK) return st;
     FinishArgs f{};
-    f.slots = g->slots; f.nslots = small_num_slots(); f.epoch = g->epoch;
+    f.slots = g->slots; f.nslots = 3 * small_num_slots(); f.epoch = g->epoch;
     f.first = g->fold_first ? 1 : 0;
     f.tie_counter = g->tie_counter;
     f.run = g->run; f.run_host = &g->h_out->run; f.best_x = g->best_x;
@@ -1336,7 +1405,8 @@ extern "C" bsse_status bsse_set_timing(bsse_game *g, int enabled)
     g_err[0] = 0;
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
     DeviceGuard dg(g->device);
-    HIP_TRY(hipStreamSynchronize(g->stream));
+    bsse_status st0 = sync_all(g);
+    if (st0 != BSSE_OK) return st0;
     for (hipEvent_t e : g->ev) g->ev_pool.push_back(e);
     g->ev.clear();
     g->timed_ms = 0.0; g->timed_launches = 0;
@@ -1349,8 +1419,9 @@ extern "C" bsse_status bsse_get_timing(bsse_game *g, double *kernel_ms_out, int6
     g_err[0] = 0;
     if (!g || !kernel_ms_out || !launches_out) return fail(BSSE_EINVAL, "NULL argument");
     DeviceGuard dg(g->device);
-    HIP_TRY(hipStreamSynchronize(g->stream));
-    bsse_status st = drain_timing(g);
+    bsse_status st = sync_all(g);
+    if (st != BSSE_OK) return st;
+    st = drain_timing(g);
     if (st != BSSE_OK) return st;
     *kernel_ms_out = g->timed_ms;
     *launches_out = g->timed_launches;
