@@ -186,6 +186,11 @@ bsse_status bsse_sweep_best_row(bsse_game *g, float *x_out);
  *   bsse_sweep_dirichlet        resets, sweeps, waits and reports like bsse_sweep;
  *   bsse_sweep_dirichlet_chunk  the streamed form, like bsse_sweep_chunk (row first + r has global
  *                               index index_base + r); report with bsse_sweep_result.
+ * Chunks of generated rows read nothing the caller's stream produces, so the handle may run them
+ * on streams of its own (default priority), ordered behind the work enqueued on the handle's
+ * stream before them; the next bsse_sweep_result / bsse_sweep_best_row / bsse_sweep_reset + chunk
+ * makes the handle's stream wait for them.  Work the caller enqueues on its stream in between is
+ * therefore not ordered after such chunks until one of those calls.
  * first, count >= 0, count <= 2^31; BSSE_EOVERFLOW if first + count or index_base + count
  * overflows. */
 bsse_status bsse_sweep_dirichlet(bsse_game *g, uint64_t seed, int64_t first, int64_t count,
