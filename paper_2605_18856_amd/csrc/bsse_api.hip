@@ -76,6 +76,13 @@ struct PriorScratch {
     }
 };
 
+// Device scratch of the top-k entry point: kept by the handle and grown on demand.
+struct TopkScratch {
+    void *p[9] = { nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr };
+    size_t cap[9] = { 0, 0, 0, 0, 0, 0, 0, 0, 0 };
+    void release() { for (void *q : p) (void)hipFree(q); }
+};
+
 struct bsse_game {
     int m = 0, n = 0, K = 0, storage = 0, device = 0;
     PathKind path = PATH_VALU;
@@ -111,6 +118,7 @@ struct bsse_game {
     unsigned long long *tie_counter = nullptr;
     float *win_l = nullptr;  // [K] per-type leader payoffs of the re-evaluated winner
     PriorScratch pri;
+    TopkScratch topk;
     // host copies of the game as given to create (fp32, unrounded): the profile LP of bsse_polish
     std::vector<float> hA, hB, hprior;
     float *stage = nullptr;                        // generated rows on their way into a sweep
@@ -183,6 +191,7 @@ void free_game(bsse_game *g)
     (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
     (void)hipFree(g->win_l);
     g->pri.release();
+    g->topk.release();
     (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
     for (int q = 0; q < 2; ++q) {
         if (g->aux[q]) { (void)hipStreamSynchronize(g->aux[q]); (void)hipStreamDestroy(g->aux[q]); }
@@ -1037,6 +1046,11 @@ extern "C" bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_d
 // --------------------------------------------------------------------------------- top-k
 namespace {
 
+struct DevView {                     // a block of handle-owned scratch
+    void *p = nullptr;
+    template <typename T> T *as() const { return reinterpret_cast<T *>(p); }
+};
+
 struct DevBuf {                      // device scratch of one call, released on every exit path
     void *p = nullptr;
     ~DevBuf() { (void)hipFree(p); }
@@ -1063,16 +1077,26 @@ extern "C" bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev
     const long long chunk = count < (1LL << 26) ? count : (1LL << 26);
     const long long nchunks = (count + chunk - 1) / chunk;
     const long long rec0 = topk_level_blocks(chunk) * k;          // records after the first level
-    DevBuf V, av, ai, bv, bi, wv, wi, rows, br;
-    HIP_TRY(hipMalloc(&V.p, (size_t)chunk * sizeof(float)));
-    HIP_TRY(hipMalloc(&av.p, (size_t)rec0 * sizeof(float)));
-    HIP_TRY(hipMalloc(&ai.p, (size_t)rec0 * sizeof(long long)));
-    HIP_TRY(hipMalloc(&bv.p, (size_t)rec0 * sizeof(float)));
-    HIP_TRY(hipMalloc(&bi.p, (size_t)rec0 * sizeof(long long)));
-    HIP_TRY(hipMalloc(&wv.p, (size_t)(nchunks + 1) * k * sizeof(float)));
-    HIP_TRY(hipMalloc(&wi.p, (size_t)(nchunks + 1) * k * sizeof(long long)));
-    HIP_TRY(hipMalloc(&rows.p, (size_t)k * m * sizeof(float)));
-    HIP_TRY(hipMalloc(&br.p, (size_t)k * K * sizeof(int32_t)));
+    // scratch of the handle, grown on demand (allocating and freeing per call costs more than the call)
+    DevView V, av, ai, bv, bi, wv, wi, rows, br;
+    {
+        DevView *views[9] = { &V, &av, &ai, &bv, &bi, &wv, &wi, &rows, &br };
+        const size_t need[9] = { (size_t)chunk * sizeof(float), (size_t)rec0 * sizeof(float),
+                                 (size_t)rec0 * sizeof(long long), (size_t)rec0 * sizeof(float),
+                                 (size_t)rec0 * sizeof(long long), (size_t)(nchunks + 1) * k * sizeof(float),
+                                 (size_t)(nchunks + 1) * k * sizeof(long long), (size_t)k * m * sizeof(float),
+                                 (size_t)k * K * sizeof(int32_t) };
+        for (int q = 0; q < 9; ++q) {
+            if (need[q] > g->topk.cap[q]) {
+                HIP_TRY(hipStreamSynchronize(g->stream));   // nothing enqueued may still use the old block
+                (void)hipFree(g->topk.p[q]);
+                g->topk.p[q] = nullptr; g->topk.cap[q] = 0;
+                HIP_TRY(hipMalloc(&g->topk.p[q], need[q]));
+                g->topk.cap[q] = need[q];
+            }
+            views[q]->p = g->topk.p[q];
+        }
+    }
 
     // levels from `n` (value, index) records in (sv, si) down to k records, written to (dv, di)
     auto reduce_to = [&](const float *sv, const long long *si, long long n, long long index_base,
