@@ -3,8 +3,9 @@
 //
 // One kernel, applied level by level.  A workgroup takes a slice of TK_SLICE elements into
 // registers (TK_E per thread) and extracts its k best in k rounds: every thread keeps the best of
-// its elements not yet taken, a shuffle/LDS reduction finds the workgroup's best, and only the
-// owning thread rescans its registers.  The k records of every workgroup form the input of the next
+// its elements not yet taken, a shuffle/LDS reduction finds the workgroup's best (one barrier per
+// round: the wavefronts' winners are double-buffered and every thread folds them itself), and only
+// the owning thread rescans its registers.  The k records of every workgroup form the input of the next
 // level (now with explicit indices), until one workgroup is left.  Nothing is atomic, so the
 // result does not depend on scheduling.
 #include "bsse_internal.h"
@@ -15,7 +16,7 @@ namespace bsse {
 namespace {
 
 constexpr int TK_THREADS = 256;
-constexpr int TK_E = 32;
+constexpr int TK_E = 8;
 constexpr int TK_SLICE = TK_THREADS * TK_E;
 
 __device__ __forceinline__ bool tk_better(float v, long long i, float bv, long long bi)
@@ -29,9 +30,9 @@ __global__ void __launch_bounds__(TK_THREADS)
 topk_level_kernel(const float *__restrict__ vals, const long long *__restrict__ idx, long long count,
                   long long index_base, int k, float *__restrict__ out_v, long long *__restrict__ out_i)
 {
-    __shared__ float sv[TK_THREADS / 64];
-    __shared__ long long si[TK_THREADS / 64];
-    __shared__ long long win_i;
+    // per-wavefront winners of a round, double-buffered by round parity: one barrier per round
+    __shared__ float sv[2][TK_THREADS / 64];
+    __shared__ long long si[2][TK_THREADS / 64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long base = (long long)blockIdx.x * TK_SLICE;
@@ -56,6 +57,10 @@ topk_level_kernel(const float *__restrict__ vals, const long long *__restrict__ 
             if (ix[e] != LLONG_MAX && (be < 0 || tk_better(v[e], ix[e], bv, bi))) { bv = v[e]; bi = ix[e]; be = e; }
         }
     };
+    // (an index of LLONG_MAX is "nothing": it never beats a record and any record beats it)
+    auto beats = [](float ov, long long oi, float bv, long long bi) {
+        return oi != LLONG_MAX && (bi == LLONG_MAX || tk_better(ov, oi, bv, bi));
+    };
     float my_v; long long my_i; int my_e;
     rescan(my_v, my_i, my_e);
     for (int r = 0; r < k; ++r) {
@@ -65,24 +70,26 @@ topk_level_kernel(const float *__restrict__ vals, const long long *__restrict__ 
         for (int d = 32; d >= 1; d >>= 1) {
             const float ov = __shfl_xor(bv, d, 64);
             const long long oi = __shfl_xor(bi, d, 64);
-            if (oi != LLONG_MAX && (bi == LLONG_MAX || tk_better(ov, oi, bv, bi))) { bv = ov; bi = oi; }
+            if (beats(ov, oi, bv, bi)) { bv = ov; bi = oi; }
         }
-        if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+        const int buf = r & 1;
+        if (lane == 0) { sv[buf][wave] = bv; si[buf][wave] = bi; }
         __syncthreads();
+        // every thread folds the wavefronts' winners itself: no second barrier to broadcast the result
+        bv = sv[buf][0]; bi = si[buf][0];
+#pragma unroll
+        for (int w = 1; w < TK_THREADS / 64; ++w)
+            if (beats(sv[buf][w], si[buf][w], bv, bi)) { bv = sv[buf][w]; bi = si[buf][w]; }
         if (tid == 0) {
-            for (int w = 1; w < TK_THREADS / 64; ++w)
-                if (si[w] != LLONG_MAX && (bi == LLONG_MAX || tk_better(sv[w], si[w], bv, bi))) { bv = sv[w]; bi = si[w]; }
-            win_i = bi;
             out_v[(size_t)blockIdx.x * k + r] = bv;
             out_i[(size_t)blockIdx.x * k + r] = bi;
         }
-        __syncthreads();
-        const long long w_i = win_i;
-        if (w_i != LLONG_MAX && my_e >= 0 && my_i == w_i) {     // indices are distinct: one owner
+        if (bi != LLONG_MAX && my_e >= 0 && my_i == bi) {       // indices are distinct: one owner
             taken |= 1u << my_e;
             rescan(my_v, my_i, my_e);
         }
-        __syncthreads();                                         // win_* may be rewritten next round
+        // (round r + 1 writes the other buffer; round r + 2 writes this one again, after everybody
+        // has passed the barrier of round r + 1 and so has finished reading it)
     }
 }
 
