@@ -96,6 +96,7 @@ struct bsse_game {
     size_t gen_cap = 0;
     unsigned long long *lat_table = nullptr;
     size_t lat_table_cap = 0;
+    int lat_table_N = -1;        // resolution the table on the device was built for (-1: none)
     float *blk_v = nullptr;
     long long *blk_i = nullptr;
     // small-game kernel: per-workgroup running bests of the current sweep, folded on demand
@@ -533,29 +534,33 @@ bsse_status lattice_impl(bsse_game *g, int N, const float *centre, float radius,
     bsse_status st = bsse_lattice_count(g->m, N, &cnt);
     if (st != BSSE_OK) return st;
     const int m = g->m;
-    // W(R,q) = C(R+q-1, q-1) for q = 0..m, R = 0..N by Pascal's rule; every entry <= cnt
     const size_t tab_elems = (size_t)(m + 1) * (N + 1);
     if (tab_elems > (1ull << 27)) return fail(BSSE_EOVERFLOW, "lattice table of %zu entries is too large", tab_elems);
-    std::vector<unsigned long long> tab(tab_elems, 0ull);
-    for (int q = 1; q <= m; ++q)
-        for (int R = 0; R <= N; ++R) {
-            unsigned long long v;
-            if (q == 1 || R == 0) v = 1;
-            else v = tab[(size_t)q * (N + 1) + R - 1] + tab[(size_t)(q - 1) * (N + 1) + R];
-            tab[(size_t)q * (N + 1) + R] = v;
-        }
     DeviceGuard dg(g->device);
     if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
     if ((st = ensure_gen(g, (unsigned long long)cnt)) != BSSE_OK) return st;
-    if (tab_elems * 8 > g->lat_table_cap) {
-        HIP_TRY(hipStreamSynchronize(g->stream));
-        (void)hipFree(g->lat_table);
-        g->lat_table = nullptr; g->lat_table_cap = 0;
-        HIP_TRY(hipMalloc((void **)&g->lat_table, tab_elems * 8));
-        g->lat_table_cap = tab_elems * 8;
+    if (g->lat_table_N != N) {                    // (the table of the last resolution stays on the device)
+        // W(R,q) = C(R+q-1, q-1) for q = 0..m, R = 0..N by Pascal's rule; every entry <= cnt
+        std::vector<unsigned long long> tab(tab_elems, 0ull);
+        for (int q = 1; q <= m; ++q)
+            for (int R = 0; R <= N; ++R) {
+                unsigned long long v;
+                if (q == 1 || R == 0) v = 1;
+                else v = tab[(size_t)q * (N + 1) + R - 1] + tab[(size_t)(q - 1) * (N + 1) + R];
+                tab[(size_t)q * (N + 1) + R] = v;
+            }
+        g->lat_table_N = -1;
+        if (tab_elems * 8 > g->lat_table_cap) {
+            HIP_TRY(hipStreamSynchronize(g->stream));
+            (void)hipFree(g->lat_table);
+            g->lat_table = nullptr; g->lat_table_cap = 0;
+            HIP_TRY(hipMalloc((void **)&g->lat_table, tab_elems * 8));
+            g->lat_table_cap = tab_elems * 8;
+        }
+        HIP_TRY(hipMemcpyAsync(g->lat_table, tab.data(), tab_elems * 8, hipMemcpyHostToDevice, g->stream));
+        HIP_TRY(hipStreamSynchronize(g->stream));     // `tab` is pageable and dies with this block
+        g->lat_table_N = N;
     }
-    HIP_TRY(hipMemcpyAsync(g->lat_table, tab.data(), tab_elems * 8, hipMemcpyHostToDevice, g->stream));
-    HIP_TRY(hipStreamSynchronize(g->stream));     // `tab` is pageable and dies with this frame
     if (centre && (st = upload_centre(g, centre)) != BSSE_OK) return st;
     HIP_TRY(launch_lattice(g->lat_table, m, N, cnt, centre ? g->centre_dev : nullptr, radius, g->gen, g->stream));
     g->gen_count = cnt;
