@@ -318,11 +318,13 @@ small_finish_kernel(int K, FinishArgs f)
     float bv = -INFINITY;
     long long bi = LLONG_MAX;
     int bb = -1;
+    // (value, epoch and index are the first sixteen bytes of a slot: one load each, all of a
+    // thread's loads independent of one another)
     for (int b = tid; b < f.nslots; b += SM_WAVES * 64) {
-        if (f.slots[b].epoch != f.epoch) continue;
-        const float v = f.slots[b].value;
-        const long long i = f.slots[b].index;
-        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; bb = b; }
+        const uint4 head = *reinterpret_cast<const uint4 *>(&f.slots[b]);
+        const float v = __uint_as_float(head.x);
+        const long long i = (long long)(((unsigned long long)head.w << 32) | head.z);
+        if (head.y == f.epoch && (v > bv || (v == bv && i < bi))) { bv = v; bi = i; bb = b; }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
