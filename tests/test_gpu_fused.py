@@ -167,6 +167,41 @@ def test_random_chunkings_in_random_order(shape):
             assert np.array_equal(bsse.bsse_sweep_best_row(g), X[one.best_index].cpu().numpy())
 
 
+def test_streamed_sweep_on_a_stream_of_the_callers():
+    """The handle bound to a stream of the caller's (default priority), a buffer filled on that stream
+    between the chunks, two handles interleaved: generated chunks may run on the handles' own
+    streams, and every result still equals the one-shot sweep."""
+    import torch
+    game_a = workloads.game(2)
+    game_b = workloads.small_game(8, 8, 8, seed=5, kind="normal")
+    count = 1 << 18
+    side = torch.cuda.Stream()
+    with _make(game_a) as ga, _make(game_b) as gb:
+        ref_a = bsse.bsse_sweep_dirichlet(ga, 9, 0, 4 * count)
+        ref_b = bsse.bsse_sweep_dirichlet(gb, 9, 0, 4 * count)
+        bsse.bsse_set_stream(ga, side.cuda_stream)
+        bsse.bsse_set_stream(gb, side.cuda_stream)
+        X = torch.empty((count, 8), dtype=torch.float32, device="cuda")
+        for rounds in range(3):
+            bsse.bsse_sweep_reset(ga)
+            bsse.bsse_sweep_reset(gb)
+            with torch.cuda.stream(side):
+                for k in range(4):
+                    bsse.bsse_sweep_dirichlet_chunk(ga, 9, k * count, count, k * count)
+                    if k == 2:
+                        # a buffered chunk in the middle: rows written on the caller's stream just before
+                        bsse.bsse_dirichlet(gb, 9, k * count, count, X)
+                        bsse.bsse_sweep_chunk(gb, X, count, k * count)
+                    else:
+                        bsse.bsse_sweep_dirichlet_chunk(gb, 9, k * count, count, k * count)
+                _same(bsse.bsse_sweep_result(ga), ref_a)
+                _same(bsse.bsse_sweep_result(gb), ref_b)
+        bsse.bsse_set_stream(ga, 0)
+        bsse.bsse_set_stream(gb, 0)
+        _same(bsse.bsse_sweep_dirichlet(ga, 9, 0, 4 * count), ref_a)
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("cfg,count", [(2, 200000), (1, 30000)])
 def test_against_the_oracle_on_its_own_rows(cfg, count):
     game = workloads.game(cfg)
