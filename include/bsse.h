@@ -2,11 +2,10 @@
  * bsse.h -- C ABI of libbsse: the batched commitment sweep of a finite Bayesian
  * Stackelberg game on one AMD MI355X (gfx950).
  *
- * Subject.  The paper this library is named after carries the subject only as the
- * title of a definition box in its preamble ("Alignment Faking: Bayesian-Stackelberg
- * Equilibria") and states no formula for it; every operation below is therefore
- * defined by the textbook strong Stackelberg equilibrium of a finite Bayesian game,
- * restated here:
+ * Subject.  The paper this library is named after gives no formula, algorithm or
+ * example for the subject (it only names it, in its preamble); every operation below
+ * is therefore defined by the textbook strong Stackelberg equilibrium of a finite
+ * Bayesian game, restated here:
  *
  *   A leader (the overseer) has m actions, a follower (the model) has n actions and
  *   one of K types t with prior weight prior[t].  A_t[i][j] is the leader's payoff
@@ -122,7 +121,8 @@ bsse_status bsse_set_stream(bsse_game *g, void *hip_stream);
  * on the simplex (flat Dirichlet): component i of row c is g_i * fl32(1 / sum_i g_i) with
  * g_i = -ln(u_i), u_i = ((w_i >> 8) + 1) / 2^24, and w the output words of
  * Philox4x32-10 keyed by (seed low word, seed high word) at counter
- * (c low word, c high word, i / 4, 0), word i % 4.  Row c depends on (seed, c) only.
+ * (c low word, c high word, i / 4, 0), word i % 4.  Row c depends on (seed, c) only -- not on
+ * first, count, or the alignment of out_dev.
  * out_dev = device [count][m] fp32 written by the call (asynchronously on the
  * handle's stream), or NULL to write a handle-owned buffer that replaces any earlier
  * generated set. */
@@ -225,9 +225,9 @@ bsse_status bsse_sweep_priors(bsse_game *g, const float *candidates_dev, int64_t
  * first, lower index among equal values" (so entry 0 is bsse_sweep's answer).  1 <= k <= 256.
  * values_out = host [k] (the kernels' fp32 values, widened), indices_out = host [k],
  * best_response_out = host [k][K] int32 or NULL; *found_out = min(k, count) entries are written.
- * The handle's prior is used.  Waits for the stream; allocates scratch (4 bytes per candidate of
- * a chunk of at most 2^26, plus records) for the duration of the call; does not touch the
- * running best of the streamed sweep. */
+ * The handle's prior is used.  Waits for the stream; its scratch (4 bytes per candidate of a
+ * chunk of at most 2^26, plus records) is allocated on first use, grown when a later call needs
+ * more, and kept until bsse_destroy; does not touch the running best of the streamed sweep. */
 bsse_status bsse_sweep_topk(bsse_game *g, const float *candidates_dev, int64_t count, int k,
                             double *values_out, int64_t *indices_out, int32_t *best_response_out,
                             int *found_out);
@@ -261,8 +261,9 @@ bsse_status bsse_refine(bsse_game *g, int k, int rounds, int lattice_N, int64_t 
  * when the profile is a best response to no x (x_out, value_out untouched).  BSSE_EOVERFLOW when
  * m * (2 + K(n-1) + m) exceeds 2^28, BSSE_ESTATE if the method does not converge.
  *
- * bsse_polish: polishes the result of the last completed sweep of the handle (BSSE_ESTATE if
- * none).  profile = host [K], or NULL for the winner's own best responses.  Solves the program
+ * bsse_polish: polishes the result of the last completed sweep of the handle: the one
+ * bsse_sweep / bsse_sweep_dirichlet / bsse_sweep_result last reported, with no chunk or reset
+ * since (BSSE_ESTATE otherwise).  profile = host [K], or NULL for the winner's own best responses.  Solves the program
  * with the payoffs as given to create (fp32, also for BF16 storage), then evaluates, with the
  * sweep's own kernels, eight points of the segment from the program's vertex to the sweep's
  * winner (the vertex lies on the boundary of the profile's region, where rounding x to fp32 can
@@ -304,6 +305,16 @@ const char *bsse_path_name(const bsse_game *g);
  * duration in milliseconds and the number of launches since timing was enabled. */
 bsse_status bsse_set_timing(bsse_game *g, int enabled);
 bsse_status bsse_get_timing(bsse_game *g, double *kernel_ms_out, int64_t *launches_out);
+
+/* Measured ceilings of the device (diagnostics for roofline reports; no part of the sweep): what
+ * plain kernels reach on it, to be quoted beside the vendor peaks.  *stream_read_gbs: a streaming
+ * read of a 2 GiB buffer, GB/s; *mfma_bf16_tflops, *mfma_f32_tflops: a loop of independent
+ * 32x32x16 bf16 / 32x32x2 fp32 matrix-core instructions on every compute unit, TFLOP/s;
+ * *empty_launch_us: time per launch of 2000 empty kernels enqueued back to back.  device = HIP
+ * ordinal, -1 = current.  Allocates 2 GiB for the duration of the call; uses the null stream and
+ * waits for it.  All four outputs are host pointers and must not be NULL. */
+bsse_status bsse_measure_ceilings(int device, double *stream_read_gbs, double *mfma_bf16_tflops,
+                                  double *mfma_f32_tflops, double *empty_launch_us);
 
 const char *bsse_last_error(void); /* thread-local; "" if none */
 const char *bsse_status_name(bsse_status s);

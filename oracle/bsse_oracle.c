@@ -5,9 +5,8 @@
  * Stackelberg game.  It exists to check the GPU library and to be timed beside
  * it; the product never calls it.  It shares no code with the GPU path.
  *
- * The paper this repository is named after carries the subject only as a box
- * title in its preamble ("Alignment Faking: Bayesian-Stackelberg Equilibria");
- * it states no formula for it.  What is computed here is therefore the textbook
+ * The paper this repository is named after only names the subject (in its
+ * preamble) and states no formula for it.  What is computed here is therefore the textbook
  * definition of the strong Stackelberg equilibrium of a finite Bayesian game,
  * evaluated by brute force over a given candidate list:
  *
@@ -109,16 +108,6 @@ double bsse_oracle_value_under_profile(int m, int n, int K, const double *A,
     }
     if (abs_scale) *abs_scale = S;
     return V;
-}
-
-/* Follower payoffs of one candidate for one type, u[j] for j<n (fp64, i ascending). */
-void bsse_oracle_follower_payoffs(int m, int n, const double *Bt, const double *x, double *u)
-{
-    for (int j = 0; j < n; ++j) {
-        double s = 0.0;
-        for (int i = 0; i < m; ++i) s += x[i] * Bt[(size_t)i * n + j];
-        u[j] = s;
-    }
 }
 
 /*

@@ -45,6 +45,12 @@ def philox4x32_10(ctr, key):
     return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
 
 
+def word_to_uniform(w) -> np.ndarray:
+    """A 32-bit generator word to u = ((w >> 8) + 1) / 2^24: the top 24 bits, shifted into (0, 1]."""
+    w = np.asarray(w, dtype=np.uint32)
+    return ((w >> np.uint32(8)).astype(np.float64) + 1.0) / 16777216.0
+
+
 def uniforms(seed: int, first: int, count: int, m: int) -> np.ndarray:
     """u[count][m] in (0,1], float64 (each value is an integer multiple of 2^-24)."""
     rows = np.arange(first, first + count, dtype=np.uint64)
@@ -55,7 +61,7 @@ def uniforms(seed: int, first: int, count: int, m: int) -> np.ndarray:
     ctr[:, :, 2] = np.arange(nb, dtype=np.uint32)[None, :]
     key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint32)
     w = philox4x32_10(ctr, key).reshape(count, nb * 4)[:, :m]
-    return ((w >> np.uint32(8)).astype(np.float64) + 1.0) / 16777216.0
+    return word_to_uniform(w)
 
 
 def rows(seed: int, first: int, count: int, m: int) -> np.ndarray:

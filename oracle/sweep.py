@@ -30,9 +30,6 @@ def _load():
         lib.bsse_oracle_value_under_profile.argtypes = [
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
-        lib.bsse_oracle_follower_payoffs.restype = None
-        lib.bsse_oracle_follower_payoffs.argtypes = [
-            ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -102,13 +99,3 @@ def value_under_profile(A, prior, x, br):
     v = _load().bsse_oracle_value_under_profile(m, n, K, _p(A), _p(prior), _p(x), _p(br),
                                                 ctypes.byref(s))
     return v, s.value
-
-
-def follower_payoffs(Bt, x):
-    """u[j] = sum_i x[i]*Bt[i][j] for one type (fp64)."""
-    Bt = np.ascontiguousarray(Bt, dtype=np.float64)
-    m, n = Bt.shape
-    x = np.ascontiguousarray(x, dtype=np.float64)
-    u = np.empty(n, np.float64)
-    _load().bsse_oracle_follower_payoffs(m, n, _p(Bt), _p(x), _p(u))
-    return u

@@ -26,7 +26,7 @@ EXPORTS = [
     "bsse_get_timing", "bsse_last_error", "bsse_status_name", "bsse_sweep_priors",
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
     "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised", "bsse_sweep_dirichlet",
-    "bsse_sweep_dirichlet_chunk", "bsse_sweep_best_row",
+    "bsse_sweep_dirichlet_chunk", "bsse_sweep_best_row", "bsse_measure_ceilings",
 ]
 
 
@@ -95,6 +95,8 @@ def lib():
     L.bsse_path_name.restype = ctypes.c_char_p
     L.bsse_set_timing.argtypes = [vp, i32]
     L.bsse_get_timing.argtypes = [vp, P(ctypes.c_double), P(i64)]
+    L.bsse_measure_ceilings.argtypes = [i32, P(ctypes.c_double), P(ctypes.c_double), P(ctypes.c_double),
+                                        P(ctypes.c_double)]
     L.bsse_last_error.argtypes = []
     L.bsse_last_error.restype = ctypes.c_char_p
     L.bsse_status_name.argtypes = [i32]
@@ -448,3 +450,13 @@ def bsse_get_timing(g: Game):
     ms, n = ctypes.c_double(), ctypes.c_int64()
     _check(lib().bsse_get_timing(g.handle, ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def bsse_ceilings(device: int = -1) -> dict:
+    """What plain kernels reach on the device (see bsse_measure_ceilings)."""
+    d = [ctypes.c_double() for _ in range(4)]
+    st = lib().bsse_measure_ceilings(int(device), *[ctypes.byref(x) for x in d])
+    if st != BSSE_OK:
+        raise BsseError(st, "bsse_measure_ceilings failed")
+    return {"stream_read_GBs": d[0].value, "mfma_bf16_TFLOPs": d[1].value,
+            "mfma_f32_TFLOPs": d[2].value, "empty_launch_us": d[3].value}

@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbsse.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["bsse_api.hip", "gen_kernels.hip", "sweep_valu.hip", "sweep_mfma.hip", "sweep_small.hip", "reduce.hip", "prior_batch.hip", "profile_lp.hip", "topk.hip"]
+SOURCES = ["bsse_api.hip", "gen_kernels.hip", "sweep_valu.hip", "sweep_mfma.hip", "sweep_small.hip", "reduce.hip", "prior_batch.hip", "profile_lp.hip", "topk.hip", "ceilings.hip"]
 HEADERS = [os.path.join(CSRC, "bsse_internal.h"), os.path.join(CSRC, "mfma_device.h"),
            os.path.join(os.path.dirname(HERE), "include", "bsse.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

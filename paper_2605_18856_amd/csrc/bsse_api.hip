@@ -83,6 +83,23 @@ struct TopkScratch {
     void release() { for (void *q : p) (void)hipFree(q); }
 };
 
+// Device scratch of the streamed sweep: one record per workgroup of a chunk, the running best, the
+// winning row, the tie counter, the per-type leader payoffs of the re-evaluated winner and (small-
+// game kernel) the workgroups' running-best slots.  Owned by the handle and grown on demand, or
+// (`fixed`) a carving of the library's static scratch array that cannot grow.
+struct Work {
+    float *blk_v = nullptr;
+    long long *blk_i = nullptr;
+    long long blk_cap = 0;
+    SmallSlot *slots = nullptr;      // slot_sets sets of small_num_slots() slots
+    int slot_sets = 0;
+    RunningBest *run = nullptr;
+    float *best_x = nullptr;
+    unsigned long long *tie_counter = nullptr;
+    float *win_l = nullptr;          // [K]
+    bool fixed = false;
+};
+
 struct bsse_game {
     int m = 0, n = 0, K = 0, storage = 0, device = 0;
     PathKind path = PATH_VALU;
@@ -97,10 +114,8 @@ struct bsse_game {
     unsigned long long *lat_table = nullptr;
     size_t lat_table_cap = 0;
     int lat_table_N = -1;        // resolution the table on the device was built for (-1: none)
-    float *blk_v = nullptr;
-    long long *blk_i = nullptr;
+    Work w;                      // the scratch in use
     // small-game kernel: per-workgroup running bests of the current sweep, folded on demand
-    SmallSlot *slots = nullptr;
     unsigned epoch = 0;          // of the current sweep (slots of other epochs are stale)
     bool fold_pending = false;   // chunks swept since the last fold
     bool fold_first = true;      // the next fold is the first of its sweep
@@ -113,11 +128,6 @@ struct bsse_game {
     hipEvent_t aux_fork = nullptr, aux_join[2] = { nullptr, nullptr };
     bool aux_used[2] = { false, false };           // work enqueued since the last join
     unsigned chunk_seq = 0;                        // chunks of the current sweep
-    long long blk_cap = 0;
-    RunningBest *run = nullptr;
-    float *best_x = nullptr;
-    unsigned long long *tie_counter = nullptr;
-    float *win_l = nullptr;  // [K] per-type leader payoffs of the re-evaluated winner
     PriorScratch pri;
     TopkScratch topk;
     // host copies of the game as given to create (fp32, unrounded): the profile LP of bsse_polish
@@ -132,6 +142,7 @@ struct bsse_game {
     int32_t *h_br = nullptr;
     long long n_evals = 0;
     bool fresh = true;       // the next chunk starts a new sweep
+    bool result_valid = false;   // bsse_sweep_result has reported the sweep in the handle's own scratch
     // kernel timing
     bool timing = false;
     std::vector<hipEvent_t> ev;      // start/stop pairs of recorded launches
@@ -188,9 +199,9 @@ void free_game(bsse_game *g)
     (void)hipFree(g->dB); (void)hipFree(g->dAT); (void)hipFree(g->dprior);
     (void)hipFree(g->dBpack); (void)hipFree(g->dATpack);
     (void)hipFree(g->gen); (void)hipFree(g->lat_table);
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i); (void)hipFree(g->slots);
-    (void)hipFree(g->run); (void)hipFree(g->best_x); (void)hipFree(g->tie_counter);
-    (void)hipFree(g->win_l);
+    (void)hipFree(g->w.blk_v); (void)hipFree(g->w.blk_i); (void)hipFree(g->w.slots);
+    (void)hipFree(g->w.run); (void)hipFree(g->w.best_x); (void)hipFree(g->w.tie_counter);
+    (void)hipFree(g->w.win_l);
     g->pri.release();
     g->topk.release();
     (void)hipFree(g->pol_rows); (void)hipFree(g->pol_v); (void)hipFree(g->pol_br);
@@ -209,14 +220,17 @@ void free_game(bsse_game *g)
 
 bsse_status ensure_blocks(bsse_game *g, long long nblocks)
 {
-    if (nblocks <= g->blk_cap) return BSSE_OK;
+    if (nblocks <= g->w.blk_cap) return BSSE_OK;
+    if (g->w.fixed)
+        return fail(BSSE_EOVERFLOW, "%lld workgroup records exceed the %lld the static scratch holds",
+                    nblocks, g->w.blk_cap);
     // the stream may still be reading the old workspace
     HIP_TRY(hipStreamSynchronize(g->stream));
-    (void)hipFree(g->blk_v); (void)hipFree(g->blk_i);
-    g->blk_v = nullptr; g->blk_i = nullptr; g->blk_cap = 0;
-    HIP_TRY(hipMalloc((void **)&g->blk_v, (size_t)nblocks * sizeof(float)));
-    HIP_TRY(hipMalloc((void **)&g->blk_i, (size_t)nblocks * sizeof(long long)));
-    g->blk_cap = nblocks;
+    (void)hipFree(g->w.blk_v); (void)hipFree(g->w.blk_i);
+    g->w.blk_v = nullptr; g->w.blk_i = nullptr; g->w.blk_cap = 0;
+    HIP_TRY(hipMalloc((void **)&g->w.blk_v, (size_t)nblocks * sizeof(float)));
+    HIP_TRY(hipMalloc((void **)&g->w.blk_i, (size_t)nblocks * sizeof(long long)));
+    g->w.blk_cap = nblocks;
     return BSSE_OK;
 }
 
@@ -415,13 +429,16 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
             if (st == BSSE_OK) st = up(&g->dATpack, pa, ab);
             free(pb); free(pa);
             if (st != BSSE_OK) break;
+            hipError_t pe = mfma_prepare(variant, K);
+            if (pe != hipSuccess) { st = fail(BSSE_EDEVICE, "mfma_prepare: %s", hipGetErrorString(pe)); break; }
         }
-        if ((st = zeroed((void **)&g->run, sizeof(RunningBest))) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->best_x, (size_t)m * 4)) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->tie_counter, 8)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->w.run, sizeof(RunningBest))) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->w.best_x, (size_t)m * 4)) != BSSE_OK) break;
+        if ((st = zeroed((void **)&g->w.tie_counter, 8)) != BSSE_OK) break;
         if (use_mfma && mfma_is_small(variant) &&       // epoch 0 marks a slot never written
-            (st = zeroed((void **)&g->slots, (size_t)3 * small_num_slots() * sizeof(SmallSlot))) != BSSE_OK) break;
-        if ((st = zeroed((void **)&g->win_l, (size_t)K * 4)) != BSSE_OK) break;
+            (st = zeroed((void **)&g->w.slots, (size_t)3 * small_num_slots() * sizeof(SmallSlot))) != BSSE_OK) break;
+        g->w.slot_sets = g->w.slots ? 3 : 0;
+        if ((st = zeroed((void **)&g->w.win_l, (size_t)K * 4)) != BSSE_OK) break;
         hipError_t e = hipHostMalloc((void **)&g->h_out, sizeof(HostOut), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc((void **)&g->h_br, (size_t)K * 4, hipHostMallocDefault);
         if (e != hipSuccess) { st = fail(BSSE_ENOMEM, "hipHostMalloc: %s", hipGetErrorString(e)); break; }
@@ -636,6 +653,7 @@ extern "C" bsse_status bsse_sweep_reset(bsse_game *g)
     DeviceGuard dg(g->device);
     if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
     g->fresh = true;          // consumed by the merge kernel of the next chunk: no launch here
+    g->result_valid = false;
     g->n_evals = 0;
     return BSSE_OK;
 }
@@ -707,10 +725,10 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
             if (g->epoch == 0) g->epoch = 1;         // 0 is the mark of a slot never written
             g->fold_first = true;
             g->chunk_seq = 0;
-            if (g->ties_dirty) HIP_TRY(launch_clear_u64(g->tie_counter, g->stream));   // an abandoned sweep's
+            if (g->ties_dirty) HIP_TRY(launch_clear_u64(g->w.tie_counter, g->stream));   // an abandoned sweep's
         }
-        int set = 2;                                 // the caller's stream
-        if (a.gen && g->chunk_seq > 0) {
+        int set = g->w.slot_sets - 1;                // the caller's stream (the last set)
+        if (a.gen && g->chunk_seq > 0 && g->w.slot_sets == 3) {
             // (the first chunk stays on the caller's stream, so a one-chunk sweep pays for no events)
             if ((st = ensure_aux(g)) != BSSE_OK) return st;
             set = (int)(g->chunk_seq & 1u);
@@ -722,12 +740,12 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
             stream = g->aux[set];
         }
         g->chunk_seq += 1;
-        a.small.slots = g->slots + (size_t)set * small_num_slots(); a.small.epoch = g->epoch;
-        a.tie_counter = g->tie_counter;
+        a.small.slots = g->w.slots + (size_t)set * small_num_slots(); a.small.epoch = g->epoch;
+        a.tie_counter = g->w.tie_counter;
     } else {
         nblocks = sweep_blocks(g, count);
         if ((st = ensure_blocks(g, nblocks)) != BSSE_OK) return st;
-        a.blk_v = g->blk_v; a.blk_i = g->blk_i; a.tie_counter = g->tie_counter;
+        a.blk_v = g->w.blk_v; a.blk_i = g->w.blk_i; a.tie_counter = g->w.tie_counter;
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (g->timing) {
@@ -744,11 +762,12 @@ bsse_status sweep_chunk_impl(bsse_game *g, SweepArgs a)
     if (small) {
         g->fold_pending = true; g->ties_dirty = true;
     } else {
-        HIP_TRY(launch_reduce_merge(g->blk_v, g->blk_i, nblocks, a.X, a.index_base, g->m,
-                                    g->fresh ? 1 : 0, g->tie_counter, g->run, &g->h_out->run, g->best_x,
+        HIP_TRY(launch_reduce_merge(g->w.blk_v, g->w.blk_i, nblocks, a.X, a.index_base, g->m,
+                                    g->fresh ? 1 : 0, g->w.tie_counter, g->w.run, &g->h_out->run, g->w.best_x,
                                     g->stream));
     }
     g->fresh = false;
+    g->result_valid = false;  // until bsse_sweep_result has brought the new state to the host
     g->n_evals += count * g->K;
     return BSSE_OK;
 }
@@ -761,10 +780,10 @@ bsse_status fold_small(bsse_game *g)
     bsse_status st = join_aux(g);
     if (st != BSSE_OK) return st;
     FinishArgs f{};
-    f.slots = g->slots; f.nslots = 3 * small_num_slots(); f.epoch = g->epoch;
+    f.slots = g->w.slots; f.nslots = g->w.slot_sets * small_num_slots(); f.epoch = g->epoch;
     f.first = g->fold_first ? 1 : 0;
-    f.tie_counter = g->tie_counter;
-    f.run = g->run; f.run_host = &g->h_out->run; f.best_x = g->best_x;
+    f.tie_counter = g->w.tie_counter;
+    f.run = g->w.run; f.run_host = &g->h_out->run; f.best_x = g->w.best_x;
     f.win_v = &g->h_out->fin_v; f.win_br = g->h_br;
     HIP_TRY(launch_finish_small(g->view, f, g->stream));
     g->fold_pending = false; g->fold_first = false; g->ties_dirty = false;
@@ -873,10 +892,10 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
         if (st != BSSE_OK) return st;
     } else {
         SweepArgs a{};
-        a.X = g->best_x; a.count = 1; a.index_base = 0;
+        a.X = g->w.best_x; a.count = 1; a.index_base = 0;
         a.V_out = &g->h_out->fin_v; a.br_out = g->h_br;
         // one row against every type: the general matrix-core kernel spreads the types over the chip
-        if (g->path != PATH_VALU && mfma_slices_types(g->view.variant)) a.l_out = g->win_l;
+        if (g->path != PATH_VALU && mfma_slices_types(g->view.variant)) a.l_out = g->w.win_l;
         HIP_TRY(launch_sweep(g, a, true));
     }
     HIP_TRY(hipStreamSynchronize(g->stream));
@@ -889,6 +908,7 @@ extern "C" bsse_status bsse_sweep_result(bsse_game *g, bsse_result *res, int32_t
     res->n_evals = g->n_evals;
     res->n_tie_evals = (int64_t)g->h_out->run.ties;
     if (has && best_response_out) memcpy(best_response_out, g->h_br, (size_t)g->K * 4);
+    g->result_valid = has && !g->w.fixed;
     return BSSE_OK;
 }
 
@@ -905,7 +925,7 @@ extern "C" bsse_status bsse_sweep_best_row(bsse_game *g, float *x_out)
     }
     HIP_TRY(hipStreamSynchronize(g->stream));
     if (g->fresh || !g->h_out->run.has) return fail(BSSE_ESTATE, "no candidate has been swept since the last reset");
-    HIP_TRY(hipMemcpy(x_out, g->best_x, (size_t)g->m * sizeof(float), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(x_out, g->w.best_x, (size_t)g->m * sizeof(float), hipMemcpyDeviceToHost));
     return BSSE_OK;
 }
 
@@ -1298,8 +1318,8 @@ extern "C" bsse_status bsse_polish(bsse_game *g, const int32_t *profile, float *
     g_err[0] = 0;
     if (!g) return fail(BSSE_EINVAL, "game is NULL");
     if (!x_out || !res) return fail(BSSE_EINVAL, "NULL argument");
-    if (g->fresh || !g->h_out || !g->h_out->run.has)
-        return fail(BSSE_ESTATE, "no sweep result to polish: call bsse_sweep (or _chunk and _result) first");
+    if (!g->result_valid)
+        return fail(BSSE_ESTATE, "no sweep result to polish: call bsse_sweep (or _chunk and then _result) first");
     const int m = g->m, n = g->n, K = g->K;
     if (profile) {
         bsse_status st = check_profile(n, K, profile);
@@ -1315,7 +1335,7 @@ extern "C" bsse_status bsse_polish(bsse_game *g, const int32_t *profile, float *
     std::vector<int32_t> brs((size_t)kPolishRows * K);
     std::vector<double> x((size_t)m);
     memcpy(prof.data(), profile ? profile : g->h_br, (size_t)K * sizeof(int32_t));
-    HIP_TRY(hipMemcpy(start.data(), g->best_x, (size_t)m * sizeof(float), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(start.data(), g->w.best_x, (size_t)m * sizeof(float), hipMemcpyDeviceToHost));
     double v_lp = 0.0;
     const int rc = solve_profile_lp(m, n, K, g->hA.data(), g->hB.data(), g->hprior.data(), prof.data(),
                                     x.data(), &v_lp);

@@ -110,6 +110,7 @@ int mfma_select(int m, int n, int K, int mode, bool exact);
 const char *mfma_variant_name(int variant);
 long long mfma_num_blocks(int variant, long long count);
 hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s);
+hipError_t mfma_prepare(int variant, int K);   // per game, on its device, before the first launch
 bool mfma_slices_types(int variant);   // the variant honours SweepArgs::l_out
 bool mfma_is_small(int variant);       // the small-game kernel: launch_finish_small applies
 // Host-side packing of payoffs for a variant; returns malloc'ed buffers (caller frees).

@@ -96,11 +96,17 @@ dirichlet_quad_kernel(unsigned k0, unsigned k1, long long first, long long count
     }
 }
 
-// Any m: one thread per row, two passes over the generator (sum, then normalise).
+// Any m, any alignment: one thread per row, two passes over the generator (sum, then normalise).
+// TREE (m a multiple of four with m/4 a power of two <= 64, the shapes the quad kernel takes): the
+// row sum is formed in the quad kernel's order -- each quad as (g0 + g1) + (g2 + g3), then the
+// quads pairwise level by level -- so that a row's bits do not depend on which kernel wrote it
+// (the quad kernel needs a 16-byte aligned output; this one does not).
+template <bool TREE>
 __global__ void __launch_bounds__(256)
 dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count, int m,
                      const float *__restrict__ centre, float radius, float omr, float *__restrict__ out)
 {
+#pragma clang fp contract(off)
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < count; r += stride) {
         const long long row = first + r;
@@ -108,11 +114,23 @@ dirichlet_row_kernel(unsigned k0, unsigned k1, long long first, long long count,
         const unsigned c1 = (unsigned)((unsigned long long)row >> 32);
         const int nb = (m + 3) / 4;
         float sum = 0.0f;
-        for (int b = 0; b < nb; ++b) {
-            const U4 w = philox4x32_10(U4{ c0, c1, (unsigned)b, 0u }, k0, k1);
-            const unsigned ww[4] = { w.x, w.y, w.z, w.w };
-            for (int e = 0; e < 4; ++e)
-                if (4 * b + e < m) sum += unit_exponential(ww[e]);
+        if (TREE) {
+            float qs[64];
+            for (int b = 0; b < nb; ++b) {
+                float g0, g1, g2, g3;
+                dirichlet_quad_raw(row, (unsigned)b, k0, k1, g0, g1, g2, g3);
+                qs[b] = dirichlet_quad_sum(g0, g1, g2, g3);
+            }
+            for (int d = 1; d < nb; d <<= 1)
+                for (int b = 0; b < nb; b += 2 * d) qs[b] = qs[b] + qs[b + d];
+            sum = qs[0];
+        } else {
+            for (int b = 0; b < nb; ++b) {
+                const U4 w = philox4x32_10(U4{ c0, c1, (unsigned)b, 0u }, k0, k1);
+                const unsigned ww[4] = { w.x, w.y, w.z, w.w };
+                for (int e = 0; e < 4; ++e)
+                    if (4 * b + e < m) sum += unit_exponential(ww[e]);
+            }
         }
         const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;                // correctly rounded
         for (int b = 0; b < nb; ++b) {
@@ -134,9 +152,8 @@ hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int
     const unsigned k0 = (unsigned)(seed & 0xFFFFFFFFull), k1 = (unsigned)(seed >> 32);
     int nb = m / 4, log2_nb = 0;
     while ((1 << log2_nb) < nb) ++log2_nb;
-    const bool quad_ok = (m % 4 == 0) && nb >= 1 && (1 << log2_nb) == nb && nb <= 64 &&
-                         ((uintptr_t)out % 16 == 0);
-    if (quad_ok) {
+    const bool quad_shape = (m % 4 == 0) && nb >= 1 && (1 << log2_nb) == nb && nb <= 64;
+    if (quad_shape && (uintptr_t)out % 16 == 0) {
         const long long quads = count * nb;
         long long blocks = (quads + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
@@ -145,8 +162,12 @@ hipError_t launch_dirichlet(uint64_t seed, long long first, long long count, int
     } else {
         long long blocks = (count + 255) / 256;
         if (blocks > 256 * 32) blocks = 256 * 32;
-        hipLaunchKernelGGL(dirichlet_row_kernel, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
-                           first, count, m, centre, radius, 1.0f - radius, out);
+        if (quad_shape)
+            hipLaunchKernelGGL(dirichlet_row_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
+                               first, count, m, centre, radius, 1.0f - radius, out);
+        else
+            hipLaunchKernelGGL(dirichlet_row_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, k0, k1,
+                               first, count, m, centre, radius, 1.0f - radius, out);
     }
     return hipGetLastError();
 }

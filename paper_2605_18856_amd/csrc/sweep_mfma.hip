@@ -775,6 +775,23 @@ long long mfma_num_blocks(int variant, long long count)
     return (count + per - 1) / per;
 }
 
+// Once per game, on the game's device: kernels whose two stage buffers exceed the default 48 KiB of
+// dynamic LDS get their limit raised here, not at every launch.
+hipError_t mfma_prepare(int variant, int K)
+{
+    if (variant == kSmallVariant) return hipSuccess;
+    if (variant < 0 || variant >= kNumVariants) return hipErrorNotSupported;
+    const Variant *v = &kVariants[variant];
+    const int tiles = row_tiles_for(*v, K);
+    const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
+    const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
+    if (lds <= 48 * 1024) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void *)v->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)v->sliced, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    return e;
+}
+
 hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t s)
 {
     if (a.count <= 0) return hipSuccess;
@@ -784,12 +801,7 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
     const int tiles = row_tiles_for(*v, g.K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
-    auto kernel = a.l_out ? v->sliced : v->kernel;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    auto kernel = a.l_out ? v->sliced : v->kernel;     // (mfma_prepare has raised their LDS limit)
     if (!a.l_out) {
         const long long blocks = mfma_num_blocks(g.variant, a.count);
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);

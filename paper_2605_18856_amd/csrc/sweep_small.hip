@@ -154,9 +154,11 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                 for (int ct = 0; ct < SM_NT; ++ct)
                     acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc[ct], 0, 0, 0);
 
-            // (the asm blocks below read acc[0] first; its last MFMA is followed by one more MFMA,
-            // whose sixteen passes cover the wait states a vector read of an MFMA result needs,
-            // which the compiler does not insert in front of inline asm; acc[1] is read later still)
+            // The asm blocks below read the accumulators, and the compiler's hazard handling does
+            // not look into inline asm: no MFMA may sink below this point, and the wait states a
+            // vector read of a fresh sixteen-pass MFMA result needs (passes + 3 = 19) are explicit.
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_nop 15\n\ts_nop 3");
             float gm[SM_NT][2], l[SM_NT][2];
             int idx[SM_NT][2];
             bool single[SM_NT][2];      // wave-uniform: every lane has exactly one maximiser

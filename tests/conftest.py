@@ -25,3 +25,29 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter, exitstatus, config):
+    """Totals of the parity comparisons of this run: evaluations compared, best-response
+    mismatches by class, and how often the sweep's winner was the oracle's own."""
+    try:
+        from tests import parity
+    except Exception:  # pragma: no cover
+        return
+    ev = [r for r in parity.LOG if r["kind"] == "eval"]
+    wn = [r for r in parity.LOG if r["kind"] == "winner"]
+    if not ev and not wn:
+        return
+    tot = {k: sum(r[k] for r in ev) for k in ("n_evals", "br_mismatch", "flagged", "bound_explained", "hard")}
+    terminalreporter.write_line(
+        "parity totals: %d comparisons, %d evaluations, %d best-response mismatches "
+        "(%d flagged gap<1e-6*s, %d bound-explained, %d hard); winner index equal to the oracle's in "
+        "%d of %d sweeps" % (len(ev), tot["n_evals"], tot["br_mismatch"], tot["flagged"],
+                              tot["bound_explained"], tot["hard"],
+                              sum(r["same_index"] for r in wn), len(wn)))
+    out = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(out):
+        import json
+        with open(os.path.join(out, "parity_counts.json"), "w") as f:
+            json.dump({"totals": tot, "winner_checks": len(wn),
+                       "winner_same_index": sum(r["same_index"] for r in wn), "log": parity.LOG}, f)

@@ -2,10 +2,14 @@
 smoke() and nothing in the product).
 
 Best responses must agree exactly except where the oracle's own follower-payoff gap between
-its best and second-best action is below 1e-6 of the dot-product scale s (flagged), or below
-the worst-case fp32 accumulation bound 2*m*2^-24*s (bound-explained); anything else is a hard
-failure.  Values are compared under the GPU's own best-response profile wherever that
-profile differs, relative to sum_t p_t sum_i |x_i A_t[i][j_t]|.
+its best and second-best action is below 1e-6 of the dot-product scale s: those are flagged and
+counted, and must stay rare.  A second class is counted apart and must be EMPTY unless a test
+states a budget for it: mismatches whose gap lies between 1e-6*s and the worst-case fp32
+accumulation bound 2*m*2^-24*s (bound-explained; the bound exceeds 1e-6 only for m >= 9).
+Anything else is a hard failure.  Values are compared under the GPU's own best-response profile
+wherever that profile differs, relative to sum_t p_t sum_i |x_i A_t[i][j_t]|.
+
+Every comparison is appended to LOG; tests/conftest.py prints the totals at the end of the run.
 """
 from dataclasses import dataclass
 
@@ -38,10 +42,12 @@ def oracle_inputs(game, X):
     return game.A, game.B, X
 
 
-def compare_eval(game, X, V_gpu, br_gpu, tol=None, nthreads=8) -> ParityReport:
+def compare_eval(game, X, V_gpu, br_gpu, tol=None, nthreads=8, ref=None) -> ParityReport:
+    """ref: the oracle's result on these rows (diagnostics=True) when the caller already has it."""
     tol = tol if tol is not None else (TOL_BF16 if game.storage == "bf16" else TOL_F32)
     A, B, Xo = oracle_inputs(game, X)
-    ref = osweep.sweep(A, B, game.prior, Xo, diagnostics=True, nthreads=nthreads)
+    if ref is None:
+        ref = osweep.sweep(A, B, game.prior, Xo, diagnostics=True, nthreads=nthreads)
     C, K = br_gpu.shape
     m = game.m
     mism = br_gpu != ref.br
@@ -66,11 +72,19 @@ def compare_eval(game, X, V_gpu, br_gpu, tol=None, nthreads=8) -> ParityReport:
                         int(hard.sum()), float(err.max()) if C else 0.0, int((err > tol).sum()))
 
 
-def check_report(rep: ParityReport, tol):
+LOG = []          # one dict per comparison / winner check of this process
+
+
+def check_report(rep: ParityReport, tol, bound_budget=0, label=""):
+    LOG.append({"kind": "eval", "label": label, "n_evals": rep.n_evals, "br_mismatch": rep.br_mismatch,
+                "flagged": rep.flagged, "bound_explained": rep.bound_explained,
+                "hard": rep.hard_failures, "max_value_err": rep.max_value_err})
     assert rep.hard_failures == 0, rep
     assert rep.value_failures == 0 and rep.max_value_err <= tol, rep
-    # tolerated mismatches must stay rare
-    assert rep.flagged + rep.bound_explained <= max(2, rep.n_evals // 1000), rep
+    # flagged near-ties must stay rare; mismatches beyond the 1e-6 rule are not tolerated at all
+    # unless the caller states how many the accumulation bound may explain
+    assert rep.flagged <= max(2, rep.n_evals // 1000), rep
+    assert rep.bound_explained <= bound_budget, rep
 
 
 def check_winner(game, X, outcome, V_gpu, tol=None):
@@ -85,4 +99,12 @@ def check_winner(game, X, outcome, V_gpu, tol=None):
     _, sc = osweep.value_under_profile(A, game.prior, Xo[outcome.best_index].astype(np.float64),
                                        ref.br[outcome.best_index])
     assert ref.values[outcome.best_index] >= ref.best_value - tol * max(sc, 1e-30)
-    return outcome.best_index == ref.best_index
+    same = outcome.best_index == ref.best_index
+    LOG.append({"kind": "winner", "same_index": bool(same), "gpu_index": int(outcome.best_index),
+                "oracle_index": int(ref.best_index),
+                "oracle_value_deficit": float(ref.best_value - ref.values[outcome.best_index])})
+    if not same:
+        # two candidates whose oracle values differ by less than the kernel's rounding: the GPU's
+        # choice is one the tolerance allows; it must at least be the arg-max of its own values
+        assert V_gpu[outcome.best_index] >= V_gpu[ref.best_index]
+    return same

@@ -23,7 +23,7 @@ MFMA_SHAPES = [
     (128, 256, 2, "f32"), (100, 256, 1, "f32"),
     (16, 32, 3, "bf16"), (32, 16, 5, "bf16"), (9, 32, 2, "bf16"),
     (64, 128, 4, "bf16"), (50, 128, 2, "bf16"),
-    # whole groups of eight types: the payoff-stationary kernel of the wide bf16 game
+    # the wide bf16 game with many types (several stages per launch) and a padded m
     (64, 128, 8, "bf16"), (64, 128, 24, "bf16"), (50, 128, 16, "bf16"),
 ]
 
@@ -174,11 +174,11 @@ def test_config3_fp32_mfma_path_sampled():
 
 
 def test_config4_one_chunk_sampled():
-    _sampled_check(workloads.game(4), 1 << 22, 1024)
+    _sampled_check(workloads.game(4), 1 << 22, 8192)
 
 
 def test_config5_subrange_sampled():
-    _sampled_check(workloads.game(5), 1 << 14, 256)
+    _sampled_check(workloads.game(5), 1 << 16, 4096)
 
 
 def test_config5_tie_injected_variant():
@@ -239,11 +239,86 @@ def _full_streamed(game, total, chunk):
     assert not (mism & (ref.gap[0] >= 1e-6 * ref.scale[0])).any()
     v_ref, sc = osweep.value_under_profile(A, game.prior, Xo[0].astype(np.float64), out.best_response)
     assert abs(out.best_value - v_ref) <= tol * max(sc, 1e-30)
+    return out
+
+
+def _range_sample(game, total, winner, n_first=4096, n_strided=4096, bound_budget=0):
+    """Per-candidate parity on a sample of the whole configured range: the first n_first rows, n_strided
+    rows spread evenly over all `total`, and the sweep's winner; each row is made by the device
+    generator from its global index, evaluated with per-candidate outputs, and compared with the
+    oracle on those same row bits."""
+    torch = _torch()
+    tol = parity.TOL_BF16 if game.storage == "bf16" else parity.TOL_F32
+    rows = np.unique(np.concatenate([np.arange(n_first), np.linspace(0, total - 1, n_strided).astype(np.int64),
+                                     [winner.best_index]]))
+    with _make(game) as g:
+        Xs = torch.empty((len(rows), game.m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, game.candidate_seed, 0, n_first, Xs)
+        for q in range(n_first, len(rows)):
+            bsse.bsse_dirichlet(g, game.candidate_seed, int(rows[q]), 1, Xs[q:q + 1])
+        V = torch.empty(len(rows), dtype=torch.float32, device="cuda")
+        br = torch.empty((len(rows), game.K), dtype=torch.int32, device="cuda")
+        bsse.bsse_eval(g, Xs, len(rows), V, br)
+        torch.cuda.synchronize()
+        Vh, brh = V.cpu().numpy(), br.cpu().numpy()
+        rep = parity.compare_eval(game, Xs.cpu().numpy(), Vh, brh, tol)
+        parity.check_report(rep, tol, bound_budget, label=game.name)
+        # the winner's per-candidate value and best responses are what the sweep reported
+        w = int(np.searchsorted(rows, winner.best_index))
+        assert np.float32(winner.best_value) == Vh[w] and np.array_equal(winner.best_response, brh[w])
+        # and no sampled candidate beats it
+        assert Vh.max() <= np.float32(winner.best_value)
+    return rep
 
 
 def test_config4_all_sixteen_chunks():
-    _full_streamed(workloads.game(4), 1 << 26, 1 << 22)
+    game = workloads.game(4)
+    out = _full_streamed(game, 1 << 26, 1 << 22)
+    rep = _range_sample(game, 1 << 26, out)
+    assert rep.n_evals >= 8000 * game.K
 
 
-def test_config5_whole_range_in_subranges():
-    _full_streamed(workloads.game(5), 1 << 24, 1 << 18)
+def test_config5_whole_range():
+    game = workloads.game(5)
+    out = _full_streamed(game, 1 << 24, 1 << 20)
+    rep = _range_sample(game, 1 << 24, out)
+    assert rep.n_evals >= 8000 * game.K
+
+
+def test_config3_whole_range_against_the_oracle():
+    """Config 3 is small enough for the oracle to sweep all 2^24 candidates (about 10^12 fp64
+    operations): every per-candidate value and best response is compared, and the sweep's winner
+    with the oracle's own arg-max over the whole range."""
+    torch = _torch()
+    game = workloads.game(3)
+    total, piece = 1 << 24, 1 << 21
+    tol = parity.TOL_F32
+    best = (-np.inf, -1)
+    with _make(game) as g:
+        Xd = torch.empty((total, game.m), dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, game.candidate_seed, 0, total, Xd)
+        V = torch.empty(total, dtype=torch.float32, device="cuda")
+        br = torch.empty((total, game.K), dtype=torch.int32, device="cuda")
+        bsse.bsse_eval(g, Xd, total, V, br)
+        out = bsse.bsse_sweep(g, Xd, total)
+        torch.cuda.synchronize()
+        Vh = V.cpu().numpy()
+        assert out.best_index == int(np.argmax(Vh)) and np.float32(out.best_value) == Vh[out.best_index]
+        flagged = bound = 0
+        for a in range(0, total, piece):
+            Xp = Xd[a:a + piece].cpu().numpy()
+            brp = br[a:a + piece].cpu().numpy()
+            ref = osweep.sweep(game.A, game.B, game.prior, Xp, diagnostics=True, nthreads=16)
+            rep = parity.compare_eval(game, Xp, Vh[a:a + piece], brp, tol, nthreads=16, ref=ref)
+            parity.check_report(rep, tol, bound_budget=0, label="config3 rows %d.." % a)
+            flagged += rep.flagged
+            if ref.best_value > best[0]:
+                best = (ref.best_value, a + ref.best_index)
+            print("config3 rows %d..%d compared, flagged so far %d" % (a, a + piece, flagged), flush=True)
+        # the oracle's value at the GPU's winner is within tolerance of the oracle's optimum
+        Xw = Xd[out.best_index:out.best_index + 1].cpu().numpy()
+        rw = osweep.sweep(game.A, game.B, game.prior, Xw, diagnostics=True)
+        _, sc = osweep.value_under_profile(game.A, game.prior, Xw[0].astype(np.float64), rw.best_br)
+        assert rw.best_value >= best[0] - tol * sc
+        print("config3 whole range: gpu winner %d, oracle winner %d, flagged %d of %d evaluations"
+              % (out.best_index, best[1], flagged, total * game.K), flush=True)

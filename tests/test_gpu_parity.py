@@ -111,6 +111,25 @@ def test_dirichlet_rows_against_oracle(m):
         assert np.array_equal(bsse.candidates_to_host(g), X[500:])
 
 
+@pytest.mark.parametrize("m", [4, 8, 32, 64, 256])
+def test_dirichlet_rows_do_not_depend_on_output_alignment(m):
+    """An output buffer that is only 4-byte aligned takes another generation kernel; the rows are
+    the same bits (row c is a function of the seed and c alone)."""
+    torch = _torch()
+    game = workloads.small_game(m, 2, 1, 1)
+    seed, first, count = 77, 12345, 777
+    with _make(game) as g:
+        aligned = torch.empty((count, m), dtype=torch.float32, device="cuda")
+        flat = torch.zeros(count * m + 4, dtype=torch.float32, device="cuda")
+        bsse.bsse_dirichlet(g, seed, first, count, aligned)
+        for off in (1, 2, 3):
+            view = flat[off:off + count * m]
+            assert view.data_ptr() % 16 != 0
+            bsse.bsse_dirichlet(g, seed, first, count, view)
+            torch.cuda.synchronize()
+            assert torch.equal(view.view(count, m), aligned)
+
+
 # --------------------------------------------------------------------- VALU path, shapes
 VALU_SHAPES = [(3, 3, 2), (8, 8, 4), (5, 7, 3), (1, 4, 2), (4, 1, 3), (16, 33, 2), (70, 9, 2),
                (300, 5, 2)]

@@ -99,6 +99,22 @@ def test_polish_state_and_argument_errors():
         with pytest.raises(bsse.BsseError) as e:
             bsse.bsse_polish(g, profile=[0, 3])
         assert e.value.status == bsse.BSSE_EINVAL
+        # a chunk swept since the last reported result: there is no completed sweep to polish
+        for gm in (game, workloads.small_game(8, 8, 4, seed=6, kind="normal")):     # VALU and small-game paths
+            with _make(gm) as h:
+                bsse.bsse_lattice(h, 5)
+                bsse.bsse_sweep(h)
+                bsse.bsse_polish(h)
+                bsse.bsse_sweep_chunk(h, None, 0, 0)
+                with pytest.raises(bsse.BsseError) as e:
+                    bsse.bsse_polish(h)
+                assert e.value.status == bsse.BSSE_ESTATE
+                bsse.bsse_sweep_result(h)
+                bsse.bsse_polish(h)
+                bsse.bsse_sweep_reset(h)
+                with pytest.raises(bsse.BsseError) as e:
+                    bsse.bsse_polish(h)
+                assert e.value.status == bsse.BSSE_ESTATE
 
 
 @pytest.mark.parametrize("shape,count", [((3, 3, 2), 4000), ((4, 3, 3), 20000), ((5, 4, 2), 20000),

@@ -127,3 +127,35 @@ def test_dirichlet_around_is_the_affine_image():
     assert np.allclose(loc, 0.75 * c[None, :].astype(np.float64) + 0.25 * base, rtol=0, atol=1e-15)
     assert np.allclose(loc.sum(axis=1), 1.0, atol=1e-12)
     assert np.array_equal(dirichlet.rows_around(11, 5, 40, 4, c, 1.0), base)
+
+
+def test_word_to_uniform_map_by_hand():
+    """u = ((w >> 8) + 1) / 2^24: the low eight bits are dropped, the result lies in (0, 1]."""
+    w = np.array([0x00000000, 0x000000FF, 0x00000100, 0x7FFFFFFF, 0x80000000, 0xFFFFFF00, 0xFFFFFFFF],
+                 dtype=np.uint32)
+    u = dirichlet.word_to_uniform(w)
+    assert list(u) == [2.0 ** -24, 2.0 ** -24, 2.0 ** -23, 0.5, 0.5 + 2.0 ** -24, 1.0, 1.0]
+
+
+def test_uniforms_from_the_first_known_answer_vector():
+    """Seed 0, row 0, block 0 is the all-zero counter and key of the first published vector, whose
+    output words are 6627e8d5 e169c58d bc57ac4c 9b00dbd8.  Dropping the low byte of each and adding
+    one gives, by hand, the numerators 6694889, 14772678, 12343213, 10158300 over 2^24."""
+    u = dirichlet.uniforms(0, 0, 1, 4)
+    assert list(u[0] * 16777216.0) == [6694889.0, 14772678.0, 12343213.0, 10158300.0]
+    # m = 3 takes the first three words; m = 5 starts a second block with counter word 2 = 1
+    assert list(dirichlet.uniforms(0, 0, 1, 3)[0]) == list(u[0, :3])
+    w1 = dirichlet.philox4x32_10(np.array([0, 0, 1, 0], np.uint32), np.array([0, 0], np.uint32))
+    assert dirichlet.uniforms(0, 0, 1, 5)[0, 4] == ((int(w1[0]) >> 8) + 1) / 16777216.0
+
+
+def test_uniforms_counter_and_key_layout():
+    """Row index in counter words 0 (low) and 1 (high), block in word 2, word 3 zero; seed low and
+    high words as the key: checked through the generator's core, which the published vectors pin."""
+    seed, row = 0x0123456789ABCDEF, (7 << 32) + 5
+    u = dirichlet.uniforms(seed, row, 2, 12)
+    for r in range(2):
+        for b in range(3):
+            w = dirichlet.philox4x32_10(np.array([(row + r) & 0xFFFFFFFF, (row + r) >> 32, b, 0], np.uint32),
+                                        np.array([0x89ABCDEF, 0x01234567], np.uint32))
+            assert list(u[r, 4 * b:4 * b + 4]) == [((int(x) >> 8) + 1) / 16777216.0 for x in w]

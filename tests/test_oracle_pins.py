@@ -309,3 +309,91 @@ def test_empty_and_single_candidate():
     assert r.best_index == -1
     r = osweep.sweep(g.A, g.B, g.prior, np.array([[1.0, 0.0, 0.0]]))
     assert r.best_index == 0
+
+
+# ------------------------------------------------------ diagnostics: gap, scale, abs-scale
+def test_scale_and_gap_on_a_hand_case_with_cancellation():
+    """x = (1/2, 1/2); follower payoffs by hand: u = (1, 3/2, 0).  Top two actions are 1 and 0.
+    Their sums of absolute terms are |-1| + |5/2| = 7/2 and 2 + 1 = 3, so scale = 7/2 and
+    gap = 1/2.  Action 2 has the largest absolute sum (100) but is not among the top two, and
+    every action's terms cancel in part, so |sum| and sum|.| differ: a scale taken over all
+    actions (100), of the maximiser alone, or as |u| (3/2) fails here."""
+    B = np.array([[[4.0, -2.0, 100.0], [-2.0, 5.0, -100.0]]])
+    A = np.array([[[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]]])
+    r = osweep.sweep(A, B, [1.0], np.array([[0.5, 0.5]]), diagnostics=True)
+    assert r.br[0, 0] == 1
+    assert r.gap[0, 0] == 0.5
+    assert r.scale[0, 0] == 3.5
+    # runner-up with the larger absolute sum: swap the roles (u = (3/2, 1, 0); sums 3, 7/2)
+    B2 = np.array([[[5.0, -1.0, 100.0], [-2.0, 3.0, -100.0]]])
+    r2 = osweep.sweep(A, B2, [1.0], np.array([[0.5, 0.5]]), diagnostics=True)
+    assert r2.br[0, 0] == 0 and r2.gap[0, 0] == 0.5 and r2.scale[0, 0] == 3.5
+    # one action only: no runner-up
+    r1 = osweep.sweep(A[:, :, :1], B[:, :, :1], [1.0], np.array([[0.5, 0.5]]), diagnostics=True)
+    assert np.isinf(r1.gap[0, 0]) and r1.scale[0, 0] == 3.0
+
+
+def test_scale_on_a_generic_game_against_numpy():
+    g = workloads.small_game(7, 6, 3, 41, kind="normal")
+    X = workloads.host_candidates(7, 500, 42, "dirichlet").astype(np.float64)
+    r = osweep.sweep(g.A, g.B, g.prior, X, diagnostics=True)
+    B64 = g.B.astype(np.float64)
+    U = np.einsum("ci,tij->ctj", X, B64)
+    S = np.einsum("ci,tij->ctj", np.abs(X), np.abs(B64))           # sum_i |x_i B_t[i][j]| (x >= 0 or not)
+    order = np.argsort(-U, axis=2, kind="stable")
+    top2 = np.take_along_axis(S, order[:, :, :2], axis=2)
+    assert np.allclose(r.scale, top2.max(axis=2), rtol=1e-13, atol=0)
+    assert np.allclose(r.gap, np.take_along_axis(U, order[:, :, :1], 2)[:, :, 0]
+                       - np.take_along_axis(U, order[:, :, 1:2], 2)[:, :, 0], atol=1e-13)
+    # candidates with negative components: absolute values are taken of the products
+    Xn = X.copy()
+    Xn[:, ::2] *= -1.0
+    rn = osweep.sweep(g.A, g.B, g.prior, Xn, diagnostics=True)
+    Un = np.einsum("ci,tij->ctj", Xn, B64)
+    on = np.argsort(-Un, axis=2, kind="stable")
+    assert np.allclose(rn.scale, np.take_along_axis(S, on[:, :, :2], axis=2).max(axis=2), rtol=1e-13)
+
+
+def test_value_under_profile_and_its_abs_scale():
+    """Hand case: p = (1/4, 3/4), x = (1/2, 1/2); type 0 told to play the column (2, -2):
+    l = 0, sum|.| = 2; type 1 the column (-4, 1): l = -3/2, sum|.| = 5/2.
+    V = -9/8, abs-scale = 1/2 + 15/8 = 19/8 (not |V|, and not unweighted)."""
+    A = np.array([[[9.0, 2.0], [9.0, -2.0]], [[-4.0, 7.0], [1.0, 7.0]]])
+    v, s = osweep.value_under_profile(A, [0.25, 0.75], [0.5, 0.5], [1, 0])
+    assert v == -1.125 and s == 2.375
+    # generic data against numpy
+    g = workloads.small_game(9, 5, 4, 43, kind="normal")
+    rng = np.random.Generator(np.random.PCG64(44))
+    for _ in range(20):
+        x = rng.standard_normal(9)
+        br = rng.integers(0, 5, 4)
+        v, s = osweep.value_under_profile(g.A, g.prior, x, br)
+        cols = np.stack([g.A[t, :, br[t]].astype(np.float64) for t in range(4)])       # [K][m]
+        p = g.prior.astype(np.float64)
+        assert v == pytest.approx(float(p @ (cols @ x)), rel=1e-13, abs=1e-15)
+        assert s == pytest.approx(float(p @ (np.abs(cols) @ np.abs(x))), rel=1e-13)
+
+
+# --------------------------------------------------------- operand rounding fed to the oracle
+def test_round_to_bf16_matches_an_independent_conversion():
+    """The bf16 operands the oracle is fed come from workloads.round_to_bf16; PyTorch's CPU
+    float32 -> bfloat16 conversion (round to nearest, ties to even) is the independent routine."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(45))
+    vals = [rng.standard_normal(1 << 18).astype(np.float32),
+            (rng.standard_normal(1 << 16) * 1e-30).astype(np.float32),
+            (rng.standard_normal(1 << 16) * 1e30).astype(np.float32)]
+    # every finite upper half with the lower half at, just below and just above the halfway point,
+    # and at the extremes: ties go to the even upper half, everything else to the nearest
+    hi = np.arange(1 << 16, dtype=np.uint32) << np.uint32(16)
+    for lo in (0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF):
+        vals.append((hi | np.uint32(lo)).view(np.float32))
+    x = np.concatenate(vals)
+    x = x[np.isfinite(x)]
+    ours = workloads.round_to_bf16(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    fin = np.isfinite(ref)                       # values that round up to infinity: compare bits too
+    assert np.array_equal(ours.view(np.uint32), ref.view(np.uint32))
+    assert fin.sum() > 0.99 * x.size
+    assert np.array_equal(workloads.round_to_bf16(ours), ours)                # idempotent
+    assert (ours.view(np.uint32) & np.uint32(0xFFFF) == 0).all()
