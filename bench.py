@@ -98,7 +98,7 @@ def cpu_baseline_leg(game, g, count_chunk, lattice, with_parity):
         ref = osweep.sweep(A, B, game.prior, Xh, per_candidate=False, nthreads=cores)
         passes += 1
         c1 = time.perf_counter()
-        if c1 - c0 >= 12.0 or passes >= 20000 or sample < count:
+        if c1 - c0 >= 10.0 or passes >= 20000:        # (the probe over-estimates the cost per row)
             break
     n1 = int(max(16, min(sample, 3.0 / (per_row * max(cores, 1)))))
     s0 = time.perf_counter()

@@ -156,6 +156,22 @@ bsse_status bsse_candidates(bsse_game *g, const float **dev_out, int64_t *count_
 bsse_status bsse_sweep(bsse_game *g, const float *candidates_dev, int64_t count,
                        bsse_result *res, int32_t *best_response_out);
 
+/* bsse_sweep for callers that cannot allocate: code that must not call hipMalloc (tight serving
+ * loops, harnesses that forbid allocation, code that will later be captured into a HIP graph).
+ * Same arguments, same result bit for bit as bsse_sweep on the same rows, but every piece of device
+ * scratch (workgroup records, running best, winning row, tie counter, running-best slots) lives in
+ * a static device array of 1.2 MiB that each GPU the library runs on holds until the process ends;
+ * the call performs no hipMalloc / hipHostMalloc / hipFree and creates no stream or event.
+ * candidates_dev must be given (not NULL).  Limits: the chunk may need at most 65536 workgroup
+ * records (2^24 candidates on the matrix-core paths with 256 candidates per workgroup, 2^22 on
+ * the plain vector path; the small-game kernel has no such limit); more is BSSE_EOVERFLOW, with
+ * nothing enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (two handles, two streams, two threads) race on it and must be serialised by the
+ * caller.  Kernel timing (bsse_set_timing) does not cover this call.  Like bsse_sweep it resets
+ * the handle's streamed sweep; afterwards there is no result to polish (bsse_polish: BSSE_ESTATE). */
+bsse_status bsse_sweep_static(bsse_game *g, const float *candidates_dev, int64_t count,
+                              bsse_result *res, int32_t *best_response_out);
+
 /* The same sweep streamed in chunks (step 6, the running best over chunks):
  *   bsse_sweep_reset  forgets the running best;
  *   bsse_sweep_chunk  enqueues the sweep of one chunk whose row r has global index

@@ -27,6 +27,7 @@ EXPORTS = [
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
     "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised", "bsse_sweep_dirichlet",
     "bsse_sweep_dirichlet_chunk", "bsse_sweep_best_row", "bsse_measure_ceilings",
+    "bsse_sweep_static",
 ]
 
 
@@ -75,6 +76,7 @@ def lib():
     L.bsse_dirichlet.argtypes = [vp, u64, i64, i64, vp]
     L.bsse_candidates.argtypes = [vp, P(vp), P(i64)]
     L.bsse_sweep.argtypes = [vp, vp, i64, P(bsse_result), vp]
+    L.bsse_sweep_static.argtypes = [vp, vp, i64, P(bsse_result), vp]
     L.bsse_sweep_reset.argtypes = [vp]
     L.bsse_sweep_chunk.argtypes = [vp, vp, i64, i64]
     L.bsse_sweep_result.argtypes = [vp, P(bsse_result), vp]
@@ -298,6 +300,17 @@ def bsse_sweep(g: Game, candidates=None, count: Optional[int] = None) -> SweepOu
     br = np.full(g.K, -1, dtype=np.int32)
     _check(lib().bsse_sweep(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
                             ctypes.byref(res), br.ctypes.data))
+    return _outcome(g, res, br)
+
+
+def bsse_sweep_static(g: Game, candidates, count: Optional[int] = None) -> SweepOutcome:
+    """bsse_sweep through the entry point that allocates nothing (explicit candidates only)."""
+    if count is None:
+        count = candidates.numel() // g.m
+    res = bsse_result()
+    br = np.full(g.K, -1, dtype=np.int32)
+    _check(lib().bsse_sweep_static(g.handle, _dev_ptr(candidates, "float32", count * g.m), count,
+                                   ctypes.byref(res), br.ctypes.data))
     return _outcome(g, res, br)
 
 

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 using namespace bsse;
@@ -299,6 +300,53 @@ bsse_status drain_timing(bsse_game *g)
 
 }  // namespace
 
+// ---------------------------------------------------------------------- static scratch
+// Scratch of bsse_sweep_static: a file-scope device array, so that the entry point allocates
+// nothing.  Every GPU the library runs on holds its own copy (1.2 MiB) until the process ends; the
+// array's name is only a host-side stand-in, the device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what kernels and fills are given.
+namespace {
+
+constexpr long long STATIC_MAX_BLOCKS = 65536;    // workgroup records of one chunk
+constexpr int STATIC_MAX_M = 4096, STATIC_MAX_K = 65536, STATIC_MAX_SLOTS = 2048;
+constexpr size_t ST_OFF_RUN = 0, ST_OFF_TIES = 256, ST_OFF_BESTX = 512,
+                 ST_OFF_WINL = ST_OFF_BESTX + (size_t)STATIC_MAX_M * sizeof(float),
+                 ST_OFF_BLKV = ST_OFF_WINL + (size_t)STATIC_MAX_K * sizeof(float),
+                 ST_OFF_BLKI = ST_OFF_BLKV + (size_t)STATIC_MAX_BLOCKS * sizeof(float),
+                 ST_OFF_SLOTS = ST_OFF_BLKI + (size_t)STATIC_MAX_BLOCKS * sizeof(long long),
+                 STATIC_BYTES = ST_OFF_SLOTS + (size_t)STATIC_MAX_SLOTS * sizeof(SmallSlot);
+static_assert(sizeof(RunningBest) <= 256 && sizeof(SmallSlot) == 64, "scratch layout");
+static_assert(ST_OFF_WINL % 256 == 0 && ST_OFF_BLKV % 256 == 0 && ST_OFF_BLKI % 256 == 0 &&
+              ST_OFF_SLOTS % 256 == 0, "scratch parts stay 256-byte aligned");
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+unsigned char *g_scratch_ptr[MAX_DEVICES];      // per device: the address of its copy of `scratch`
+std::mutex g_scratch_mutex;
+
+// With device `dev` current: the device address of that device's scratch array (looked up on the
+// first call per device).
+bsse_status static_scratch(int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(BSSE_EDEVICE, "device ordinal %d is beyond %d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(BSSE_EDEVICE, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return BSSE_OK;
+}
+
+}  // namespace
+
 // ------------------------------------------------------------------------------ create
 extern "C" bsse_status bsse_create(int m, int n, int K, const float *A, const float *B,
                                    const float *prior, bsse_game **out)
@@ -445,6 +493,11 @@ extern "C" bsse_status bsse_create_ex(int m, int n, int K, const float *A, const
     } while (0);
     if (st != BSSE_OK) { free_game(g); return st; }
 
+    {   // set-up of the static scratch for this device (bsse_sweep_static reports a failure itself)
+        unsigned char *unused = nullptr;
+        (void)static_scratch(dev, &unused);
+        g_err[0] = 0;
+    }
     g->view.m = m; g->view.n = n; g->view.K = K;
     g->view.x_bf16 = bf ? 1 : 0;
     g->view.B = g->dB; g->view.AT = g->dAT; g->view.prior = g->dprior;
@@ -943,6 +996,71 @@ extern "C" bsse_status bsse_sweep(bsse_game *g, const float *candidates_dev, int
     }
     bsse_status st = bsse_sweep_reset(g);
     if (st != BSSE_OK) return st;
+    if ((st = bsse_sweep_chunk(g, candidates_dev, count, 0)) != BSSE_OK) return st;
+    return bsse_sweep_result(g, res, best_response_out);
+}
+
+// bsse_sweep with every piece of device scratch taken from the static array: no allocation of any
+// kind happens in this call (device, pinned host or stream/event objects).
+extern "C" bsse_status bsse_sweep_static(bsse_game *g, const float *candidates_dev, int64_t count,
+                                         bsse_result *res, int32_t *best_response_out)
+{
+    g_err[0] = 0;
+    if (!g) return fail(BSSE_EINVAL, "game is NULL");
+    if (!res) return fail(BSSE_EINVAL, "res is NULL");
+    if (!candidates_dev) return fail(BSSE_EINVAL, "candidates is NULL (the static sweep takes an explicit buffer)");
+    {
+        const float *x = candidates_dev;
+        int64_t c = count;
+        bsse_status st = resolve_candidates(g, &x, &c);
+        if (st != BSSE_OK) return st;
+    }
+    const bool small = on_small_kernel(g);
+    if (!small && sweep_blocks(g, count) > STATIC_MAX_BLOCKS)
+        return fail(BSSE_EOVERFLOW, "%lld candidates need %lld workgroup records; the static scratch holds %lld "
+                    "(sweep in pieces, or use bsse_sweep)", (long long)count, sweep_blocks(g, count),
+                    STATIC_MAX_BLOCKS);
+    if (small && small_num_slots() > STATIC_MAX_SLOTS)
+        return fail(BSSE_EOVERFLOW, "the static scratch holds %d running-best slots, %d needed", STATIC_MAX_SLOTS,
+                    small_num_slots());
+    if (g->m > STATIC_MAX_M || g->K > STATIC_MAX_K)
+        return fail(BSSE_EOVERFLOW, "the static scratch holds rows of %d and %d types", STATIC_MAX_M, STATIC_MAX_K);
+    DeviceGuard dg(g->device);
+    if (!dg.ok) return fail(BSSE_EDEVICE, "hipSetDevice failed");
+    unsigned char *ptr = nullptr;
+    bsse_status st = static_scratch(g->device, &ptr);
+    if (st != BSSE_OK) return st;
+
+    // the handle works on the static scratch for the length of this call; its own sweep state
+    // is what bsse_sweep leaves behind as well: reset
+    struct Swap {
+        bsse_game *g; Work own; bool timing, ties_dirty;
+        ~Swap()
+        {
+            g->w = own; g->timing = timing; g->ties_dirty = ties_dirty;
+            g->fresh = true; g->fold_pending = false; g->result_valid = false; g->n_evals = 0;
+        }
+    } swap{ g, g->w, g->timing, g->ties_dirty };
+    Work w;
+    w.run = reinterpret_cast<RunningBest *>(ptr + ST_OFF_RUN);
+    w.tie_counter = reinterpret_cast<unsigned long long *>(ptr + ST_OFF_TIES);
+    w.best_x = reinterpret_cast<float *>(ptr + ST_OFF_BESTX);
+    w.win_l = reinterpret_cast<float *>(ptr + ST_OFF_WINL);
+    w.blk_v = reinterpret_cast<float *>(ptr + ST_OFF_BLKV);
+    w.blk_i = reinterpret_cast<long long *>(ptr + ST_OFF_BLKI);
+    w.blk_cap = STATIC_MAX_BLOCKS;
+    w.slots = small ? reinterpret_cast<SmallSlot *>(ptr + ST_OFF_SLOTS) : nullptr;
+    w.slot_sets = small ? 1 : 0;
+    w.fixed = true;
+    g->w = w;
+    g->timing = false;              // (event pairs would be created on demand)
+    g->ties_dirty = false;
+    // the array keeps the last call's contents, possibly another handle's: the running best, the
+    // tie counter and (small-game kernel) the slots' epochs start from zero.  A fill kernel, not a
+    // memset node, so that the call stays safe to capture.
+    HIP_TRY(launch_fill_zero(ptr, ST_OFF_BESTX, g->stream));
+    if (small) HIP_TRY(launch_fill_zero(ptr + ST_OFF_SLOTS, (size_t)small_num_slots() * sizeof(SmallSlot), g->stream));
+    if ((st = bsse_sweep_reset(g)) != BSSE_OK) return st;
     if ((st = bsse_sweep_chunk(g, candidates_dev, count, 0)) != BSSE_OK) return st;
     return bsse_sweep_result(g, res, best_response_out);
 }

@@ -136,6 +136,8 @@ hipError_t launch_reduce_merge(const float *blk_v, const long long *blk_i, long 
 
 // *p = 0 by a one-thread kernel (a fill node that is safe to capture in a graph).
 hipError_t launch_clear_u64(unsigned long long *p, hipStream_t s);
+// Zero `bytes` (a multiple of 16) at the 16-byte aligned device address p, by a kernel.
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 
 // Prior batch (see prior_batch.hip): V_p[c] = sum_t priors[p][t] * L[c][t] and the arg-max over c
 // for each of P priors, merged into run[P] (first != 0: replaced).  blk_v / blk_i: workspace of

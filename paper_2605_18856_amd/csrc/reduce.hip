@@ -70,7 +70,26 @@ reduce_merge_kernel(const float *__restrict__ blk_v, const long long *__restrict
 
 __global__ void clear_u64_kernel(unsigned long long *p) { *p = 0ull; }
 
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4 *p, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 }  // namespace
+
+// bytes must be a multiple of 16 and p 16-byte aligned
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    if (bytes % 16 != 0 || ((uintptr_t)p & 15) != 0) return hipErrorInvalidValue;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4 *)p, n16);
+    return hipGetLastError();
+}
 
 hipError_t launch_clear_u64(unsigned long long *p, hipStream_t s)
 {
