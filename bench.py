@@ -39,7 +39,7 @@ EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0}
 TRAFFIC_BYTES = {
     "config2": (144.9 * 2.0 + 49.2) * 1024.0,          # rows generated in registers: slots and payoffs only
     "config3": (1070309.2 * 2.0 + 2057.8) * 1024.0,
-    "config4": (776547.9 * 2.0 + 1043.6) * 1024.0,
+    "config4": (673309.0 * 2.0 + 270.1) * 1024.0,
 }
 
 # workload -> (config number, candidates per step, candidates per chunk (= per launch), note)

@@ -265,6 +265,93 @@ __device__ __forceinline__ float vmax_chain16(float p, const float *u)
     return p;
 }
 
+
+// ---- helpers of the wide-game epilogue ---------------------------------------------------
+// Maximum of sixteen values, two independent streams interleaved (no initial value needed: the
+// first instruction of a stream takes three of its values).
+__device__ __forceinline__ void vmax16x2_first(float &pa, const float *ua, float &pb, const float *ub)
+{
+#define BSSE_U4(x, a, b, c, d) [x##a] "v"(x[a]), [x##b] "v"(x[b]), [x##c] "v"(x[c]), [x##d] "v"(x[d])
+#define BSSE_MX(a, b)                                                           \
+        "v_max3_f32 %[pa], %[pa], %[ua" #a "], %[ua" #b "]\n\t"                  \
+        "v_max3_f32 %[pb], %[pb], %[ub" #a "], %[ub" #b "]\n\t"
+    asm("v_max3_f32 %[pa], %[ua0], %[ua1], %[ua2]\n\t"
+        "v_max3_f32 %[pb], %[ub0], %[ub1], %[ub2]\n\t"
+        BSSE_MX(3, 4) BSSE_MX(5, 6) BSSE_MX(7, 8) BSSE_MX(9, 10) BSSE_MX(11, 12) BSSE_MX(13, 14)
+        "v_max_f32 %[pa], %[pa], %[ua15]\n\t"
+        "v_max_f32 %[pb], %[pb], %[ub15]"
+        : [pa] "=&v"(pa), [pb] "=&v"(pb)
+        : BSSE_U4(ua, 0, 1, 2, 3), BSSE_U4(ua, 4, 5, 6, 7), BSSE_U4(ua, 8, 9, 10, 11),
+          BSSE_U4(ua, 12, 13, 14, 15), BSSE_U4(ub, 0, 1, 2, 3), BSSE_U4(ub, 4, 5, 6, 7),
+          BSSE_U4(ub, 8, 9, 10, 11), BSSE_U4(ub, 12, 13, 14, 15));
+#undef BSSE_MX
+#undef BSSE_U4
+}
+// Element-wise maximum over four vectors of sixteen: w[r] = max(a[r], b[r], c[r], d[r]).
+__device__ __forceinline__ void vmax4x16(float *w, const float *a, const float *b, const float *c, const float *d)
+{
+#define BSSE_W4(x, i) [x##0] "v"(x[i]), [x##1] "v"(x[i + 1]), [x##2] "v"(x[i + 2]), [x##3] "v"(x[i + 3])
+#pragma unroll
+    for (int i = 0; i < 16; i += 4)
+        asm("v_max3_f32 %[w0], %[a0], %[b0], %[c0]\n\t"
+            "v_max3_f32 %[w1], %[a1], %[b1], %[c1]\n\t"
+            "v_max3_f32 %[w2], %[a2], %[b2], %[c2]\n\t"
+            "v_max3_f32 %[w3], %[a3], %[b3], %[c3]\n\t"
+            "v_max_f32 %[w0], %[w0], %[d0]\n\t"
+            "v_max_f32 %[w1], %[w1], %[d1]\n\t"
+            "v_max_f32 %[w2], %[w2], %[d2]\n\t"
+            "v_max_f32 %[w3], %[w3], %[d3]"
+            : [w0] "=&v"(w[i]), [w1] "=&v"(w[i + 1]), [w2] "=&v"(w[i + 2]), [w3] "=&v"(w[i + 3])
+            : BSSE_W4(a, i), BSSE_W4(b, i), BSSE_W4(c, i), BSSE_W4(d, i));
+}
+// w[r] = max(a[r], b[r])
+__device__ __forceinline__ void vmax2x16(float *w, const float *a, const float *b)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i += 4)
+        asm("v_max_f32 %[w0], %[a0], %[b0]\n\t"
+            "v_max_f32 %[w1], %[a1], %[b1]\n\t"
+            "v_max_f32 %[w2], %[a2], %[b2]\n\t"
+            "v_max_f32 %[w3], %[a3], %[b3]"
+            : [w0] "=&v"(w[i]), [w1] "=&v"(w[i + 1]), [w2] "=&v"(w[i + 2]), [w3] "=&v"(w[i + 3])
+            : BSSE_W4(a, i), BSSE_W4(b, i));
+#undef BSSE_W4
+}
+// bitmap16_split with every compare mask in a scalar register pair (a vector instruction that
+// takes its mask or carry from vcc issues several times slower on this part than one that takes
+// it from a scalar pair).
+__device__ __forceinline__ unsigned bitmap16_pairs(const float *u, float gmax)
+{
+    unsigned ba = 0u, bb = 0u;
+    unsigned long long m0, m1, m2, m3, m4, m5, m6, m7;
+#define BSSE_BM4S(a, b, c, d, e, f, g, h)                                       \
+        "v_cmp_eq_f32 %[m0], %[u" #a "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m1], %[u" #e "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m2], %[u" #b "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m3], %[u" #f "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m4], %[u" #c "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m5], %[u" #g "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m6], %[u" #d "], %[g]\n\t"                              \
+        "v_cmp_eq_f32 %[m7], %[u" #h "], %[g]\n\t"                              \
+        "v_addc_co_u32_e64 %[ba], %[m0], %[ba], %[ba], %[m0]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m1], %[bb], %[bb], %[m1]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m2], %[ba], %[ba], %[m2]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m3], %[bb], %[bb], %[m3]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m4], %[ba], %[ba], %[m4]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m5], %[bb], %[bb], %[m5]\n\t"               \
+        "v_addc_co_u32_e64 %[ba], %[m6], %[ba], %[ba], %[m6]\n\t"               \
+        "v_addc_co_u32_e64 %[bb], %[m7], %[bb], %[bb], %[m7]\n\t"
+    asm(BSSE_BM4S(0, 1, 2, 3, 8, 9, 10, 11) BSSE_BM4S(4, 5, 6, 7, 12, 13, 14, 15)
+        : [ba] "+v"(ba), [bb] "+v"(bb), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+          [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6), [m7] "=&s"(m7)
+        : [u0] "v"(u[0]), [u1] "v"(u[1]), [u2] "v"(u[2]), [u3] "v"(u[3]), [u4] "v"(u[4]),
+          [u5] "v"(u[5]), [u6] "v"(u[6]), [u7] "v"(u[7]), [u8] "v"(u[8]), [u9] "v"(u[9]),
+          [u10] "v"(u[10]), [u11] "v"(u[11]), [u12] "v"(u[12]), [u13] "v"(u[13]), [u14] "v"(u[14]),
+          [u15] "v"(u[15]), [g] "v"(gmax));
+#undef BSSE_BM4S
+    return (ba << 8) | bb;
+}
+
 // (a + b) over the two lanes of a candidate, same value in both (integers)
 __device__ __forceinline__ unsigned pair_add_u32(unsigned v)
 {

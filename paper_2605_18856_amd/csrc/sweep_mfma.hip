@@ -139,6 +139,60 @@ template <int MP> struct Path<__bf16, MP> {
         const float l = l0 + l1;
         return l;
     }
+    // The same sum in two steps -- the lane's half of the column into registers, then the dot
+    // product -- so that a caller can put other work between the reads and their use.  Same
+    // instruction sequence on the same values as half_dot, hence the same bits.
+    typedef u32x4 colregs[XREGS / 4];
+    __device__ static __forceinline__ void gather_half(const lds_byte *col, colregs &c)
+    {
+        const __attribute__((address_space(3))) u32x4 *p = (const __attribute__((address_space(3))) u32x4 *)col;
+#pragma unroll
+        for (int e = 0; e < XREGS / 4; ++e) c[e] = p[e];
+    }
+    __device__ static __forceinline__ float half_dot_regs(const xreg *x, const colregs &c)
+    {
+        float l0 = 0.0f, l1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < XREGS; e += 4) {
+            const unsigned w0 = c[e / 4][0], w1 = c[e / 4][1], w2 = c[e / 4][2], w3 = c[e / 4][3];
+            // (a dot result feeding the next dot needs no wait states; the three that another kind
+            // of vector instruction needs follow the last group only)
+            asm volatile("v_dot2c_f32_bf16 %0, %2, %6\n\t"
+                         "v_dot2c_f32_bf16 %1, %3, %7\n\t"
+                         "v_dot2c_f32_bf16 %0, %4, %8\n\t"
+                         "v_dot2c_f32_bf16 %1, %5, %9"
+                         : "+v"(l0), "+v"(l1)
+                         : "v"(x[e]), "v"(x[e + 1]), "v"(x[e + 2]), "v"(x[e + 3]), "v"(w0), "v"(w1), "v"(w2), "v"(w3));
+        }
+        asm volatile("s_nop 2" : "+v"(l0), "+v"(l1));
+        return l0 + l1;
+    }
+    // Two candidate tiles at once: the four accumulation chains are interleaved (a dot product
+    // feeding the next one of its chain waits for it), each chain as in half_dot_regs.
+    __device__ static __forceinline__ void half_dot_regs2(const xreg *xa, const colregs &ca, const xreg *xb,
+                                                          const colregs &cb, float &la, float &lb)
+    {
+        float a0 = 0.0f, a1 = 0.0f, b0 = 0.0f, b1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < XREGS; e += 4) {
+            const unsigned p0 = ca[e / 4][0], p1 = ca[e / 4][1], p2 = ca[e / 4][2], p3 = ca[e / 4][3];
+            const unsigned q0 = cb[e / 4][0], q1 = cb[e / 4][1], q2 = cb[e / 4][2], q3 = cb[e / 4][3];
+            asm volatile("v_dot2c_f32_bf16 %0, %4, %8\n\t"
+                         "v_dot2c_f32_bf16 %2, %12, %16\n\t"
+                         "v_dot2c_f32_bf16 %1, %5, %9\n\t"
+                         "v_dot2c_f32_bf16 %3, %13, %17\n\t"
+                         "v_dot2c_f32_bf16 %0, %6, %10\n\t"
+                         "v_dot2c_f32_bf16 %2, %14, %18\n\t"
+                         "v_dot2c_f32_bf16 %1, %7, %11\n\t"
+                         "v_dot2c_f32_bf16 %3, %15, %19"
+                         : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1)
+                         : "v"(xa[e]), "v"(xa[e + 1]), "v"(xa[e + 2]), "v"(xa[e + 3]), "v"(p0), "v"(p1), "v"(p2), "v"(p3),
+                           "v"(xb[e]), "v"(xb[e + 1]), "v"(xb[e + 2]), "v"(xb[e + 3]), "v"(q0), "v"(q1), "v"(q2), "v"(q3));
+        }
+        asm volatile("s_nop 2" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1));
+        la = a0 + a1;
+        lb = b0 + b1;
+    }
     // The same sum when the column holds three identical blocks (payoffs that are bf16 numbers,
     // against the three parts of x): each 16 bytes of the first block are loaded once and used
     // for all three parts, instead of gathering the same values three times.
@@ -194,6 +248,13 @@ __host__ __device__ constexpr Geometry make_geometry(int esz, int mp, int n, int
     const int unit = waves * 1024;
     q.rec_bytes = (stage_tiles * q.tile_bytes + q.at_bytes + unit - 1) / unit * unit;
     return q;
+}
+
+// dynamic LDS of sweep_wide_kernel: two fragment buffers and two leader-row buffers
+__host__ __device__ constexpr int wide_lds_bytes(int esz, int mp, int n, int waves)
+{
+    const Geometry q = make_geometry(esz, mp, n, n / 32, waves, true);
+    return 2 * (q.tpg * q.tile_bytes) + 2 * ((q.at_bytes + 1023) / 1024 * 1024);
 }
 
 typedef const void __attribute__((address_space(1))) *global_ptr;
@@ -661,6 +722,354 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
 }
 
+
+// ------------------------------------------------------------------------------------------
+// The same sweep for wide games (N a multiple of 32 with two or four row tiles per type; leader
+// rows in LDS; one type per stage).  Every wavefront sweeps TWO pairs of candidate tiles against
+// each staged type, one pair after the other, so a workgroup of four wavefronts covers 512
+// candidates per copy of the packed payoffs: stage copies (global memory -> LDS) slow the matrix
+// pipe down roughly in proportion to the bytes a compute unit copies, and this halves them.  The
+// fragments and the leader rows of a stage have LDS buffers of their own, two each; the one
+// workgroup barrier per type stands at the start of the type, behind it the other buffers are free
+// and the copies issued one type ago have landed, so a copy has a whole type to arrive.
+// Epilogue: both candidate tiles of a pair advance together, stage by stage, so that every
+// exchange with the partner lane (through the LDS crossbar) and every gather is in flight while
+// the other tile's vector work is issued: per-tile lane maxima (which row tile holds the maximum)
+// and element-wise maxima across the row tiles (which register position holds it); a unique
+// maximiser is one tile and one position, anything else goes to the exact routine.  Arithmetic,
+// operand order, packing and the exact-tie routine are those of sweep_mfma_kernel: the same bits
+// per candidate.
+template <typename T, int MP, int N, int WAVES, int PF>
+__global__ void __launch_bounds__(WAVES * 64, 2)
+sweep_wide_kernel(GameView g, SweepArgs a, int row_tiles)
+{
+    constexpr int NT = 2, NP = 2;              // candidate tiles per pass, passes per staged type
+    typedef Path<T, MP> P;
+    typedef typename P::frag frag;
+    typedef typename P::xreg xreg;
+    constexpr int KS = P::KSTEPS, HALF = P::HALF;
+    constexpr Geometry G = make_geometry((int)sizeof(T), MP, N, N / 32, WAVES, true);
+    constexpr int TPG = G.tpg;
+    static_assert(N % 32 == 0 && (TPG == 2 || TPG == 4) && G.ts == 1, "one type of two or four row tiles per stage");
+    static_assert(std::is_same<T, __bf16>::value, "bf16 matrix cores");
+    constexpr int TILE_FRAGS = KS * 64;
+    constexpr int FRAG_BYTES = TPG * G.tile_bytes;                      // the stage's fragments
+    constexpr int LROW_CHUNKS = (G.at_bytes + 1023) / 1024;             // its leader rows, in 1 KiB copies
+    constexpr int LROW_BYTES = LROW_CHUNKS * 1024;
+    static_assert(FRAG_BYTES % (WAVES * 1024) == 0 && FRAG_BYTES + LROW_BYTES <= G.rec_bytes, "record layout");
+    constexpr int NCH = TPG * KS / PF;                                  // fragment chunks per type
+    static_assert(PF > 0 && KS % PF == 0 && NCH % 2 == 0, "chunk 0 of every pass lands in the same registers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // F[2], then L[2]
+    __shared__ float red_v[WAVES];
+    __shared__ long long red_i[WAVES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, col = lane & 31;
+    const int m = g.m, K = g.K;
+    const unsigned char *records = reinterpret_cast<const unsigned char *>(g.Bpack);
+    const unsigned char *ATpack = reinterpret_cast<const unsigned char *>(g.ATpack);
+    const long long wave_base = ((long long)blockIdx.x * WAVES + wave) * (NP * NT * 32);
+    const int partner_addr = 4 * (lane ^ 32);
+    (void)row_tiles;
+
+    auto copy_stage = [&](int st, int buf) __attribute__((always_inline)) {
+        const unsigned char *src = records + (size_t)st * G.rec_bytes;
+        unsigned char *dstF = smem + buf * FRAG_BYTES;
+        unsigned char *dstL = smem + 2 * FRAG_BYTES + buf * LROW_BYTES;
+#pragma unroll
+        for (int i = 0; i < FRAG_BYTES / (WAVES * 1024); ++i) {
+            const int chunk = i * WAVES + wave;
+            __builtin_amdgcn_global_load_lds((global_ptr)(src + chunk * 1024 + lane * 16),
+                                             (lds_ptr)(dstF + chunk * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < (LROW_CHUNKS + WAVES - 1) / WAVES; ++i) {
+            const int chunk = i * WAVES + wave;
+            if (chunk < LROW_CHUNKS)                                     // wave-uniform
+                __builtin_amdgcn_global_load_lds((global_ptr)(src + FRAG_BYTES + chunk * 1024 + lane * 16),
+                                                 (lds_ptr)(dstL + chunk * 1024), 16, 0, 0);
+        }
+    };
+    copy_stage(0, 0);
+
+    // ---- candidate rows into registers (as in sweep_mfma_kernel), both passes
+    constexpr int HALF_BASE = MP / 2;
+    xreg x[NP][NT][P::XREGS];
+    unsigned valid32[NP][NT];
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            const long long c = wave_base + (ps * NT + ct) * 32 + col;
+            const bool ok = c < a.count;
+            float vb[HALF_BASE];
+            const float *row = a.X + (ok ? c : 0) * (long long)m + h * HALF_BASE;
+            if (m == MP && HALF_BASE % 4 == 0 && ((uintptr_t)a.X & 15) == 0) {
+#pragma unroll
+                for (int e = 0; e < HALF_BASE; e += 4) {
+                    f32x4 q = ok ? *(const f32x4 *)(row + e) : f32x4{ 0, 0, 0, 0 };
+                    vb[e] = q[0]; vb[e + 1] = q[1]; vb[e + 2] = q[2]; vb[e + 3] = q[3];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < HALF_BASE; ++e) vb[e] = (ok && h * HALF_BASE + e < m) ? row[e] : 0.0f;
+            }
+            P::pack_x(vb, x[ps][ct]);
+            valid32[ps][ct] = (unsigned)__builtin_amdgcn_ballot_w64(ok);
+        }
+
+    float V[NP][NT];
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) V[ps][ct] = 0.0f;
+    unsigned tie_count = 0;                   // wave-uniform
+
+    // Exact routine for one (candidate tile, type), as in sweep_mfma_kernel: the type's tiles once
+    // more from the packed records in global memory (same instructions, same bits), the exact
+    // maximisers in ascending action order, the leader's payoff decides and then the lower action.
+    auto exact_type = [&](const xreg *xc, unsigned valid, int t, float gmax, float &l_out, int &j_out) __attribute__((always_inline)) {
+        float lbest = 0.0f;
+        int jbest = 0, nmatch = 0;
+        const unsigned char *ATt = ATpack + (size_t)t * N * MP * sizeof(T);
+#pragma unroll 1
+        for (int tt = 0; tt < TPG; ++tt) {
+            const frag *afrags = reinterpret_cast<const frag *>(
+                records + (size_t)t * G.rec_bytes + (size_t)tt * G.tile_bytes);
+            f32x16 acc1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) acc1 = P::mfma(afrags[s * 64 + lane], xc, s, acc1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int r = 4 * q + rr;
+                        const int j = tt * 32 + acc_row_base(r) + 4 * hh;
+                        const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc1[r] == gmax);
+                        const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid;
+                        if (hit == 0u) continue;                       // wave-uniform
+                        const float l = pair_sum(P::half_dot(xc, ATt + ((size_t)j * MP + h * HALF) * sizeof(T)));
+                        if ((hit >> col) & 1u) {
+                            if (nmatch == 0 || l > lbest) { lbest = l; jbest = j; }
+                            ++nmatch;
+                        }
+                    }
+        }
+        l_out = lbest; j_out = jbest;
+        tie_count += __builtin_popcount((unsigned)__builtin_amdgcn_ballot_w64(nmatch >= 2));
+    };
+
+    f32x16 acc[NT][TPG];
+    frag fb[2][PF];
+    auto read_chunk = [&](const frag *lane_base, auto qc, frag (&dst)[PF]) __attribute__((always_inline)) {
+        constexpr int q = decltype(qc)::value;
+#pragma unroll
+        for (int e = 0; e < PF; ++e) {
+            constexpr int f0 = q * PF;
+            const int f = f0 + e;                                        // flat (tile, k-step)
+            dst[e] = lane_base[(size_t)(f / KS) * TILE_FRAGS + (size_t)(f % KS) * 64];
+        }
+    };
+    // MFMAs of one type for one pair of candidate tiles; chunk 0 of the fragments is already in
+    // fb[0]; chunk q+1 is read before the MFMAs of chunk q are issued.
+    auto mfma_type = [&](const frag *lane_base, const xreg (*xp)[P::XREGS]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int tt = 0; tt < TPG; ++tt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ct][tt][r] = 0.0f;
+        static_for<0, NCH, 1>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            if constexpr (q + 1 < NCH) read_chunk(lane_base, std::integral_constant<int, q + 1>{}, fb[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, PF, 1>([&](auto ec) {
+                constexpr int f = q * PF + decltype(ec)::value;
+                constexpr int tt = f / KS, ks = f % KS;
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(fb[q & 1][decltype(ec)::value], xp[ct], ks, acc[ct][tt]);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // Epilogue of type t for one pair of candidate tiles (rows xp, validity masks vp, values Vp);
+    // leader rows of the type in Lt.
+    auto epilogue = [&](int t, float pt, const lds_byte *Lt, const xreg (*xp)[P::XREGS], const unsigned *vp,
+                        float *Vp, long long cbase) __attribute__((always_inline)) {
+        // The asm blocks read the accumulators, and the compiler's hazard handling does not look into
+        // inline asm: the wait states a vector read of a fresh MFMA result needs (passes + 3 = 11) are
+        // explicit.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15");
+        // stage 1: per-tile lane maxima and element-wise maxima across the row tiles; the lane
+        // maximum goes to the partner lane
+        float pmt[NT][TPG], w[NT][16], pm[NT], pm_other[NT];
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            float u[TPG][16];
+#pragma unroll
+            for (int tt = 0; tt < TPG; ++tt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) u[tt][r] = acc[ct][tt][r];
+            vmax16x2_first(pmt[ct][0], u[0], pmt[ct][TPG / 2], u[TPG / 2]);
+            if constexpr (TPG == 4) {
+                vmax16x2_first(pmt[ct][1], u[1], pmt[ct][3], u[3]);
+                vmax4x16(w[ct], u[0], u[1], u[2], u[3]);
+            } else {
+                vmax2x16(w[ct], u[0], u[1]);
+            }
+            float p = TPG == 4 ? vmax3(pmt[ct][0], pmt[ct][1], pmt[ct][2]) : pmt[ct][0];
+            pm[ct] = vmax2(p, pmt[ct][TPG - 1]);
+            pm_other[ct] = pair_other(pm[ct], partner_addr);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // stage 2: the pair's maximum; the tile (exactly one per lane, or the columns are marked);
+        // the position as a 16-bit map (bit 15 - r set iff position r holds the maximum); then
+        // (action | number of maximisers << 16), zero in a lane without one, goes to the partner
+        float gm[NT];
+        unsigned total[NT], total_other[NT], tile_tie[NT];
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            gm[ct] = vmax2(pm[ct], pm_other[ct]);
+            unsigned tile = 0u;
+            unsigned long long seen = 0ull, dup = 0ull;
+#pragma unroll
+            for (int k = 0; k < TPG; ++k) {
+                const bool e = pmt[ct][k] == gm[ct];
+                const unsigned long long mk = __builtin_amdgcn_ballot_w64(e);
+                dup |= seen & mk;
+                seen |= mk;
+                if (k) tile = e ? (unsigned)(32 * k) : tile;
+            }
+            tile_tie[ct] = (unsigned)(dup | (dup >> 32));
+            const unsigned bm = bitmap16_pairs(w[ct], gm[ct]);
+            const unsigned cnt = (unsigned)__builtin_popcount(bm);
+            const unsigned r = ffbh(bm) - 16u;
+            // action = 32 * tile + row(register) + 4h
+            const unsigned act = tile | ((r & 0xCu) << 1) | (r & 3u) | (4u * h);
+            total[ct] = cnt ? (cnt << 16) | act : 0u;
+            total_other[ct] = (unsigned)__builtin_amdgcn_ds_bpermute(partner_addr, (int)total[ct]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // stage 3: the action, the gather of its leader column, and whether the tile is clean
+        int js[NT];
+        bool clean[NT];
+        typename P::colregs cr[NT];
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            const unsigned pair = total[ct] + total_other[ct];
+            // (masked: a wavefront that is not clean may hold any sum here, and the gather is issued
+            // before that is known)
+            js[ct] = (int)(pair & 0xFFFFu);
+            const unsigned jg = (N & (N - 1)) == 0 ? (unsigned)js[ct] & (unsigned)(N - 1)
+                                                    : ((unsigned)js[ct] < (unsigned)N ? (unsigned)js[ct] : 0u);
+            P::gather_half(Lt + (unsigned)((jg * G.ats + h * HALF) * sizeof(T)), cr[ct]);
+            const unsigned multi = (unsigned)__builtin_amdgcn_ballot_w64((pair >> 16) != 1u) | tile_tie[ct];
+            clean[ct] = (multi & vp[ct]) == 0u && vp[ct] == 0xFFFFFFFFu;   // wave-uniform
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // stage 4: leader payoffs (each lane its half, the partner the other) and the value
+        float l[NT];
+        if (clean[0] && clean[1]) {
+            float part[NT], part_other[NT];
+            P::half_dot_regs2(xp[0], cr[0], xp[1], cr[1], part[0], part[1]);
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) part_other[ct] = pair_other(part[ct], partner_addr);
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct)
+                l[ct] = h ? part_other[ct] + part[ct] : part[ct] + part_other[ct];      // (lower half) + (upper half)
+        } else {
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                if (clean[ct]) {
+                    const float part = P::half_dot_regs(xp[ct], cr[ct]);
+                    const float other = pair_other(part, partner_addr);
+                    l[ct] = h ? other + part : part + other;
+                } else {
+                    exact_type(xp[ct], vp[ct], t, gm[ct], l[ct], js[ct]);
+                }
+            }
+        }
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) {
+            Vp[ct] = fmaf(pt, l[ct], Vp[ct]);
+            if (a.br_out) {
+                const long long c = cbase + ct * 32 + col;
+                if (h == 0 && c < a.count) a.br_out[c * K + t] = js[ct];
+            }
+        }
+    };
+
+    const frag *F0 = reinterpret_cast<const frag *>(smem) + lane;
+    const frag *F1 = reinterpret_cast<const frag *>(smem + FRAG_BYTES) + lane;
+    const lds_byte *L0 = (const lds_byte *)smem + (unsigned)(2 * FRAG_BYTES);
+#pragma unroll 1
+    for (int t = 0; t < K; ++t) {
+        // own copies of this type's stage have landed; then everyone's have, and everyone is done with
+        // the previous type, whose buffers take the next type's stage
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (t + 1 < K) copy_stage(t + 1, (t + 1) & 1);
+        const float pt = g.prior[t];
+        const frag *Ft = (t & 1) ? F1 : F0;
+        const lds_byte *Lt = L0 + (unsigned)((t & 1) * LROW_BYTES);
+        read_chunk(Ft, std::integral_constant<int, 0>{}, fb[0]);
+#pragma unroll
+        for (int ps = 0; ps < NP; ++ps) {
+            mfma_type(Ft, x[ps]);
+            if (ps + 1 < NP) read_chunk(Ft, std::integral_constant<int, 0>{}, fb[0]);   // the next pass's first fragments
+            epilogue(t, pt, Lt, x[ps], valid32[ps], V[ps], wave_base + ps * NT * 32);
+        }
+    }
+
+    // ---- outputs (as in sweep_mfma_kernel)
+    if (a.V_out) {
+#pragma unroll
+        for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                const long long c = wave_base + (ps * NT + ct) * 32 + col;
+                float v = V[ps][ct];
+                if (!(v == v)) v = -INFINITY;
+                if (h == 0 && c < a.count) a.V_out[c] = v;
+            }
+    }
+    if (a.blk_v) {
+        float bv = -INFINITY;
+        long long bi = LLONG_MAX;
+#pragma unroll
+        for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                const long long c = wave_base + (ps * NT + ct) * 32 + col;
+                float v = V[ps][ct];
+                if (!(v == v)) v = -INFINITY;
+                if (c < a.count && (v > bv || (v == bv && a.index_base + c < bi))) { bv = v; bi = a.index_base + c; }
+            }
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) {          // both lane halves hold the same values
+            const float ov = __shfl_xor(bv, d, 64);
+            const long long oi = __shfl_xor(bi, d, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w2 = 1; w2 < WAVES; ++w2)
+                if (red_v[w2] > bv || (red_v[w2] == bv && red_i[w2] < bi)) { bv = red_v[w2]; bi = red_i[w2]; }
+            a.blk_v[blockIdx.x] = bv;
+            a.blk_i[blockIdx.x] = bi;
+        }
+    }
+    if (a.tie_counter && lane == 0 && tie_count) atomicAdd(a.tie_counter, (unsigned long long)tie_count);
+}
+
 // Second step of the type-sliced evaluation: V[c] = sum_t prior[t] * l[c][t], one lane per row,
 // accumulated in type order with the fused multiply-add of the unsliced kernel, so the value is
 // the same fp32 number.
@@ -682,17 +1091,26 @@ struct Variant {
     int terms;                   // 1, or the number of part products of the split (3 or 6)
     int mp_base, n, nt, waves, stage_tiles;
     bool at_lds;
-    void (*kernel)(GameView, SweepArgs, int);
+    void (*kernel)(GameView, SweepArgs, int);     // null when `wide` sweeps this packing
     void (*sliced)(GameView, SweepArgs, int);     // one candidate tile per wavefront, types sliced
     Geometry geo;
     const char *name;
+    void (*wide)(GameView, SweepArgs, int);       // sweep_wide_kernel for this packing, or null
+    int wide_lds;                                 // its dynamic LDS bytes
 };
 
 #define BSSE_VARIANT(T, MODE, TERMSv, MPB, Nv, NTv, Wv, STv, OCCv, ATL, PFv, NAME)                   \
     { MODE, TERMSv, MPB, Nv, NTv, Wv, STv, ATL,                                                      \
       sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv, false, PFv>,           \
       sweep_mfma_kernel<T, MPB * TERMSv, Nv, 1, Wv, STv, 1, ATL, TERMSv, true, PFv>,                 \
-      make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME }
+      make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME, nullptr, 0 }
+// A packing that sweep_wide_kernel also takes (one type per stage, leader rows in LDS, NT = 2)
+#define BSSE_VARIANT_WIDE(T, MODE, MPB, Nv, Wv, PFv, NAME)                                           \
+    { MODE, 1, MPB, Nv, 2, Wv, Nv / 32, true,                                                        \
+      nullptr,                                                                                       \
+      sweep_mfma_kernel<T, MPB, Nv, 1, Wv, Nv / 32, 1, true, 1, true, PFv>,                          \
+      make_geometry((int)sizeof(T), MPB, Nv, Nv / 32, Wv, true), NAME,                               \
+      sweep_wide_kernel<T, MPB, Nv, Wv, PFv>, wide_lds_bytes((int)sizeof(T), MPB, Nv, Wv) }
 
 const Variant kVariants[] = {
     // fp32 MFMA (the last number before the name: k-steps per fragment read-ahead chunk, 0 = the
@@ -705,7 +1123,7 @@ const Variant kVariants[] = {
     // bf16 MFMA, operands rounded to bf16
     BSSE_VARIANT(__bf16, 1, 1, 16, 32, 4, 4, 2, 2, true, 0, "mfma_bf16"),
     BSSE_VARIANT(__bf16, 1, 1, 32, 16, 4, 4, 2, 2, false, 0, "mfma_bf16"),
-    BSSE_VARIANT(__bf16, 1, 1, 64, 128, 2, 4, 4, 2, true, 4, "mfma_bf16"),
+    BSSE_VARIANT_WIDE(__bf16, 1, 64, 128, 8, 4, "mfma_bf16"),
     // bf16 MFMA on fp32 operands split into bf16 parts
     BSSE_VARIANT(__bf16, 2, 6, 16, 16, 2, 4, 2, 2, true, 0, "mfma_split6"),
     BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 8, 1, 3, true, 0, "mfma_split6"),
@@ -771,7 +1189,7 @@ long long mfma_num_blocks(int variant, long long count)
 {
     if (variant == kSmallVariant) return small_num_blocks(count);
     const Variant &v = kVariants[variant];
-    const long long per = (long long)v.nt * 32 * v.waves;
+    const long long per = (long long)v.nt * 32 * v.waves * (v.wide ? 2 : 1);     // candidates per workgroup record     // candidates per workgroup record
     return (count + per - 1) / per;
 }
 
@@ -785,8 +1203,13 @@ hipError_t mfma_prepare(int variant, int K)
     const int tiles = row_tiles_for(*v, K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t lds = (size_t)v->geo.rec_bytes * (nstages > 1 ? 2 : 1);
+    if (v->wide && v->wide_lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)v->wide, hipFuncAttributeMaxDynamicSharedMemorySize, v->wide_lds);
+        if (e != hipSuccess) return e;
+    }
     if (lds <= 48 * 1024) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute((const void *)v->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipSuccess;
+    if (v->kernel) e = hipFuncSetAttribute((const void *)v->kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)v->sliced, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     return e;
@@ -804,7 +1227,10 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
     auto kernel = a.l_out ? v->sliced : v->kernel;     // (mfma_prepare has raised their LDS limit)
     if (!a.l_out) {
         const long long blocks = mfma_num_blocks(g.variant, a.count);
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
+        if (v->wide)       // (every wavefront sweeps two pairs of candidate tiles)
+            hipLaunchKernelGGL(v->wide, dim3((unsigned)blocks), dim3(v->waves * 64), (size_t)v->wide_lds, s, g, a, tiles);
+        else
+            hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(v->waves * 64), lds, s, g, a, tiles);
         return hipGetLastError();
     }
     // type-sliced evaluation: 32 candidates per wavefront, whole groups per slice; few rows are
