@@ -37,9 +37,10 @@ EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0}
 # so it is scaled by 2.0; WRITE_SIZE reads a known-size fill exactly).  Keyed by workload; one
 # launch = one chunk.
 TRAFFIC_BYTES = {
-    "config2": (144.9 * 2.0 + 49.2) * 1024.0,          # rows generated in registers: slots and payoffs only
-    "config3": (1070309.2 * 2.0 + 2057.8) * 1024.0,
+    "config2": (144.5 * 2.0 + 28.9) * 1024.0,          # rows generated in registers: slots and payoffs only
+    "config3": (1068800.0 * 2.0 + 2057.3) * 1024.0,
     "config4": (673309.0 * 2.0 + 270.1) * 1024.0,
+    "config5": (3970660.0 * 2.0 + 297.3) * 1024.0,
 }
 
 # workload -> (config number, candidates per step, candidates per chunk (= per launch), note)
