@@ -100,6 +100,104 @@ __device__ __forceinline__ void match4(float u0, float u1, float u2, float u3, f
         : "vcc");
 }
 
+// Four fp32 values as three bf16 parts each, x = x1 + x2 + x3: every part is the nearest bf16 of
+// what is left, and what is left is formed exactly (a bf16 dot product with -1 in one slot and 0
+// in the other subtracts one packed value from an fp32 number; the difference has at most 16
+// significant bits).  p12 = (x1[0..3], x2[0..3]) and p31 = (x3[0..3], x1[0..3]) as eight bf16 each,
+// the k-slot order of the small-game kernel's matrix instructions.
+__device__ __forceinline__ void split_parts(const f32x4 &x, unsigned (&p12)[4], unsigned (&p31)[4])
+{
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    // (-1, 0) and (0, -1) as packed bf16, kept in scalar registers as plain bit patterns: written
+    // as constants they may be encoded as an inline operand of the dot instruction, and what that
+    // operand expands to for a bf16 instruction is not something to rely on
+    unsigned bits_lo = 0x0000BF80u, bits_hi = 0xBF800000u;
+    asm("" : "+s"(bits_lo), "+s"(bits_hi));
+    const v2bf minus_lo = __builtin_bit_cast(v2bf, bits_lo), minus_hi = __builtin_bit_cast(v2bf, bits_hi);
+    // (a plain conversion, not inline asm: the compiler has to see the instruction to keep the
+    // wait states between it and the dot products around it)
+    auto pack = [](float a, float b) __attribute__((always_inline)) {
+        typedef float v2f __attribute__((ext_vector_type(2)));
+        const v2f ab = { a, b };
+        return __builtin_bit_cast(unsigned, __builtin_convertvector(ab, v2bf));
+    };
+    auto rest = [&](unsigned packed, float a, float b, float &ra, float &rb) __attribute__((always_inline)) {
+        const v2bf pv = __builtin_bit_cast(v2bf, packed);
+        ra = __builtin_amdgcn_fdot2_f32_bf16(pv, minus_lo, a, false);
+        rb = __builtin_amdgcn_fdot2_f32_bf16(pv, minus_hi, b, false);
+    };
+    float r[4], q[4];
+    p12[0] = pack(x[0], x[1]); p12[1] = pack(x[2], x[3]);
+    rest(p12[0], x[0], x[1], r[0], r[1]); rest(p12[1], x[2], x[3], r[2], r[3]);
+    p12[2] = pack(r[0], r[1]); p12[3] = pack(r[2], r[3]);
+    rest(p12[2], r[0], r[1], q[0], q[1]); rest(p12[3], r[2], r[3], q[2], q[3]);
+    p31[0] = pack(q[0], q[1]); p31[1] = pack(q[2], q[3]);
+    p31[2] = p12[0]; p31[3] = p12[1];
+}
+
+// Eight values and their maximum g: idx = the lowest position that holds g, n_eq = how many
+// (lane, position) pairs of the wavefront hold g (64 exactly when every lane has one maximiser).
+// Every compare mask lives in a scalar register pair (a select fed by vcc issues several times
+// slower on this part), the position is a chain of selects between inline constants from the
+// highest position down, and the count is taken on the scalar unit.  Each select stands at least
+// two instructions behind its compare.
+__device__ __forceinline__ void argmax8(float u0, float u1, float u2, float u3, float u4, float u5,
+                                        float u6, float u7, float g, unsigned &idx, unsigned &n_eq)
+{
+    unsigned long long m0, m1, m2, m3, m4, m5, m6, m7;
+    unsigned i, c, t;
+    asm("v_cmp_eq_f32 %[m6], %[u6], %[g]\n\t"
+        "v_cmp_eq_f32 %[m5], %[u5], %[g]\n\t"
+        "v_cmp_eq_f32 %[m4], %[u4], %[g]\n\t"
+        "v_cmp_eq_f32 %[m3], %[u3], %[g]\n\t"
+        "v_cmp_eq_f32 %[m2], %[u2], %[g]\n\t"
+        "v_cmp_eq_f32 %[m1], %[u1], %[g]\n\t"
+        "v_cmp_eq_f32 %[m0], %[u0], %[g]\n\t"
+        "v_cmp_eq_f32 %[m7], %[u7], %[g]\n\t"
+        "v_cndmask_b32 %[i], 7, 6, %[m6]\n\t"
+        "v_cndmask_b32 %[i], %[i], 5, %[m5]\n\t"
+        "v_cndmask_b32 %[i], %[i], 4, %[m4]\n\t"
+        "v_cndmask_b32 %[i], %[i], 3, %[m3]\n\t"
+        "v_cndmask_b32 %[i], %[i], 2, %[m2]\n\t"
+        "v_cndmask_b32 %[i], %[i], 1, %[m1]\n\t"
+        "v_cndmask_b32 %[i], %[i], 0, %[m0]\n\t"
+        "s_bcnt1_i32_b64 %[c], %[m0]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m1]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m2]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m3]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m4]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m5]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m6]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m7]\n\t"
+        "s_add_u32 %[c], %[c], %[t]"
+        : [i] "=&v"(i), [c] "=&s"(c), [t] "=&s"(t), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2),
+          [m3] "=&s"(m3), [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6), [m7] "=&s"(m7)
+        : [u0] "v"(u0), [u1] "v"(u1), [u2] "v"(u2), [u3] "v"(u3), [u4] "v"(u4), [u5] "v"(u5),
+          [u6] "v"(u6), [u7] "v"(u7), [g] "v"(g)
+        : "scc");
+    idx = i; n_eq = c;
+}
+
+// (bv, bc, bp) <- (v, c, p) in the lanes where v > bv; the mask in a scalar register pair.
+__device__ __forceinline__ void keep_greater(float v, unsigned c, unsigned p, float &bv, unsigned &bc,
+                                             unsigned &bp)
+{
+    unsigned long long m;
+    asm("v_cmp_gt_f32 %[m], %[v], %[bv]\n\t"
+        "s_nop 1\n\t"
+        "v_cndmask_b32 %[bv], %[bv], %[v], %[m]\n\t"
+        "v_cndmask_b32 %[bc], %[bc], %[c], %[m]\n\t"
+        "v_cndmask_b32 %[bp], %[bp], %[p], %[m]"
+        : [bv] "+v"(bv), [bc] "+v"(bc), [bp] "+v"(bp), [m] "=&s"(m)
+        : [v] "v"(v), [c] "v"(c), [p] "v"(p));
+}
+
 // The same for eight values in one asm block, and the running maximum over sixteen values in
 // one block: the compiler pads every boundary between two asm statements with a no-op, so
 // fewer, larger blocks save issue slots in the epilogue.

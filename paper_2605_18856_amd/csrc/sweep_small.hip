@@ -2,16 +2,27 @@
 // 4 up to 16 types, fp32): steps 2-5 in one persistent kernel that is bound by reading the
 // candidate rows (32 bytes each) once.
 //
-// Matrix-core layout.  One 32x32x2 fp32 MFMA tile holds four types x eight actions as its 32
-// rows and 32 candidates as its columns; four MFMAs (k = m = 8) finish it.  The rows are
-// ordered on the host so that the 16 rows a lane receives (accumulator rows 8q + 4h + rr in
-// register 4q + rr, h = lane/32) are the eight actions of two whole types, 2h and 2h + 1 of
-// the tile: register r holds action r % 8 of the lane's type r / 8.  Each lane therefore
-// finishes (candidate, type) pairs on its own -- maximum, lowest maximising action, leader
-// payoff -- with no cross-lane traffic; the two lane halves of a candidate cover different
-// types and their partial leader values are added once at the end.  The whole follower
-// matrix of the game is 4 registers per tile and lives in registers for the kernel's life;
-// the leader matrix sits in LDS, one padded row per (type, action).
+// Matrix-core layout.  One 32x32 tile holds four types x eight actions as its 32 rows and 32
+// candidates as its columns.  The rows are ordered on the host so that the 16 rows a lane
+// receives (accumulator rows 8q + 4h + rr in register 4q + rr, h = lane/32) are the eight
+// actions of two whole types, 2h and 2h + 1 of the tile: register r holds action r % 8 of the
+// lane's type r / 8.  Each lane therefore finishes (candidate, type) pairs on its own --
+// maximum, lowest maximising action, leader payoff -- with no cross-lane traffic; the two lane
+// halves of a candidate cover different types and their partial leader values are added once at
+// the end.
+//
+// The contraction runs on the bf16 matrix pipe at fp32 accuracy.  The fp32 matrix instruction
+// shares the vector unit's multipliers (the two never ran at the same time in the counters),
+// so its 8 cycles per candidate were added to the epilogue's vector work.  Instead each fp32
+// operand is written as the sum of three bf16 parts (x = x1 + x2 + x3, round to nearest each
+// time, the remainders exact) and the six part products that matter -- x1 b1, x2 b1, x1 b2,
+// x2 b2, x3 b1, x1 b3; the others are below 2^-25 of the product -- fill the 48 k-slots of
+// three 32x32x16 instructions (3 cycles per candidate, beside the vector unit, not in it).
+// Slot order: instruction i, lane half kh, element e: part P_i (e < 4) or Q_i (e >= 4) of
+// leader action 4 kh + (e % 4), so that a lane splits only the four components it already
+// holds for the leader payoff.  The follower parts are split on the host and stay in
+// registers for the kernel's life; the leader matrix sits in LDS, one padded row per (type,
+// action), in fp32.
 #include "bsse_internal.h"
 #include "mfma_device.h"
 #include "gen_device.h"
@@ -22,6 +33,10 @@
 namespace bsse {
 
 namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int SM_M = 8, SM_N = 8;
 constexpr int SM_WAVES = 4;
@@ -53,24 +68,40 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     const unsigned task_stride = nblocks * SM_WAVES;
 
     // candidate rows of one task: own = x[4h..4h+3] (the MFMA k-slots of this lane half),
-    // oth = the other four components (needed for the leader payoff only)
-    f32x4 own[SM_NT], oth[SM_NT];
-    auto load_task = [&](unsigned task) __attribute__((always_inline)) {
+    // oth = the other four components (needed for the leader payoff only).  Two sets of row
+    // registers take turns: while one task is worked on, the rows of the wavefront's next task
+    // land in the other set.  A task that lies wholly inside the range is addressed as a
+    // wave-uniform base plus a fixed lane offset (no vector address arithmetic); the one ragged
+    // task at the end of the range is done after the loop by the wavefront whose turn it is,
+    // with the rows past the end reading the last row instead: they are evaluated like any
+    // other and then left out of every result.
+    const unsigned lane_own = (unsigned)(col * SM_M + 4 * h) * 4u;
+    const unsigned lane_oth = (unsigned)(col * SM_M + 4 * (1 - h)) * 4u;
+    auto load_task = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
+        const char *base = reinterpret_cast<const char *>(a.X) + (size_t)task * (per_iter * SM_M * 4);
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
-            const unsigned c = task * per_iter + ct * 32 + col;
-            const bool ok = c < count;
-            const float *row = a.X + (size_t)(ok ? c : 0) * SM_M;
-            own[ct] = *(const f32x4 *)(row + 4 * h);
-            oth[ct] = *(const f32x4 *)(row + 4 * (1 - h));
-            if (!ok) { own[ct] = f32x4{ 0, 0, 0, 0 }; oth[ct] = f32x4{ 0, 0, 0, 0 }; }
+            own[ct] = *(const f32x4 *)(base + ct * 32 * SM_M * 4 + lane_own);
+            oth[ct] = *(const f32x4 *)(base + ct * 32 * SM_M * 4 + lane_oth);
         }
     };
+    auto load_ragged = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < SM_NT; ++ct) {
+            unsigned c = task * per_iter + ct * 32 + col;
+            c = c < count ? c : count - 1u;
+            const float *row = a.X + (size_t)c * SM_M;
+            own[ct] = *(const f32x4 *)(row + 4 * h);
+            oth[ct] = *(const f32x4 *)(row + 4 * (1 - h));
+        }
+    };
+    const unsigned n_full = count / per_iter;            // tasks wholly inside the range
     // GEN: the rows are made here instead.  Lane half h produces components 4h..4h+3 of its
     // candidate (the thread (row, b = h) of the generation kernel); the row sum and the other four
-    // components come from the partner lane.
+    // components come from the partner lane.  Rows past the end of the range are ordinary rows of
+    // the generator; they are left out of every result.
     const int partner_addr = 4 * (lane ^ 32);
-    auto gen_task = [&](unsigned task) __attribute__((always_inline)) {
+    auto gen_task = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
             const unsigned c = task * per_iter + ct * 32 + col;
@@ -78,13 +109,13 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             dirichlet_quad_raw(a.gen_first + (long long)c, (unsigned)h, a.gen_k0, a.gen_k1, g0, g1, g2, g3);
             const float sum = pair_sum(dirichlet_quad_sum(g0, g1, g2, g3));
             dirichlet_quad_scale(sum, SM_M, g0, g1, g2, g3);
-            const bool ok = c < count;
-            own[ct] = ok ? f32x4{ g0, g1, g2, g3 } : f32x4{ 0, 0, 0, 0 };
+            own[ct] = f32x4{ g0, g1, g2, g3 };
 #pragma unroll
             for (int k = 0; k < 4; ++k) oth[ct][k] = pair_other(own[ct][k], partner_addr);
         }
     };
-    if (!GEN && task0 < n_tasks) load_task(task0);      // first rows in flight during set-up
+    f32x4 own_a[SM_NT], oth_a[SM_NT], own_b[SM_NT], oth_b[SM_NT];
+    if (!GEN && task0 < n_full) load_task(task0, own_a, oth_a);       // first rows in flight during set-up
 
     // leader rows -> LDS (packed on the host with the padded stride); follower fragments and
     // priors -> registers
@@ -92,17 +123,25 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         const float *src = reinterpret_cast<const float *>(g.ATpack);
         for (int e = tid; e < TILES * 4 * SM_N * SM_AT_STRIDE; e += SM_WAVES * 64) at_lds[e] = src[e];
     }
-    float bfrag[TILES][4];
+    // per instruction: eight bf16 k-slots of this lane's tile row.  One row tile's fragments live
+    // in registers for the kernel's life; with more tiles they are re-read from LDS at every
+    // tile (registers for all of them cost spills in the loop).
+    constexpr bool BF_LDS = TILES >= 2;
+    __shared__ __attribute__((aligned(16))) u32x4 bf_lds[BF_LDS ? TILES * 3 * 64 : 1];
+    u32x4 bfrag[BF_LDS ? 1 : TILES][3];
     float prior[TILES][2];
     const lds_float *rows_a[TILES][2];  // this lane's (type) leader rows, own-half columns
     int oth_delta;                      // float offset from own-half to other-half columns
     const lds_float *at_l = (const lds_float *)at_lds;
     {
-        const float *src = reinterpret_cast<const float *>(g.Bpack);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(g.Bpack);
 #pragma unroll
         for (int T = 0; T < TILES; ++T) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) bfrag[T][s] = src[(T * 4 + s) * 64 + lane];
+            for (int s = 0; s < 3; ++s) {
+                if constexpr (BF_LDS) { if (wave == 0) bf_lds[(T * 3 + s) * 64 + lane] = src[(T * 3 + s) * 64 + lane]; }
+                else bfrag[T][s] = src[(T * 3 + s) * 64 + lane];
+            }
 #pragma unroll
             for (int tl = 0; tl < 2; ++tl) {
                 const int t = 4 * T + 2 * h + tl;
@@ -112,6 +151,9 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         }
         oth_delta = 4 * (1 - h) - 4 * h;
     }
+    // every set-up load has landed before the loop: the compiler would otherwise place its
+    // waits for them at their first use, inside the loop, where they also wait for row requests
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
     __syncthreads();
 
     float best_v = -INFINITY;
@@ -121,25 +163,23 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     unsigned best_pk = 0u;
     unsigned tie_count = 0;
 
-#pragma unroll 1
-    for (unsigned task = task0; task < n_tasks; task += task_stride) {
-        f32x4 xo[SM_NT], xt[SM_NT];
-        if (GEN) gen_task(task);
-#pragma unroll
-        for (int ct = 0; ct < SM_NT; ++ct) { xo[ct] = own[ct]; xt[ct] = oth[ct]; }
-        if (!GEN && task + task_stride < n_tasks) load_task(task + task_stride);   // next rows in flight
-
-        // Both candidate tiles and both of the lane's types advance together through one
-        // straight-line block (four independent dependency chains for the scheduler to
-        // interleave); the exact tie routine is a single rare branch at the end.
+    // One task: both candidate tiles and both of the lane's types advance together through one
+    // straight-line block (four independent dependency chains for the scheduler to interleave);
+    // the exact tie routine is a single rare branch per row tile.
+    auto process = [&](unsigned task, bool full, const f32x4 (&xo)[SM_NT], const f32x4 (&xt)[SM_NT]) __attribute__((always_inline)) {
+        const unsigned first = task * per_iter;
         float vhalf[SM_NT];
         unsigned pk[SM_NT];
-        bool all_ok[SM_NT];
+        // the lane's four components as three bf16 parts: k-slots (x1, x2) for the instructions
+        // against b1 and b2, (x3, x1) for the one against (b1, b3)
+        u32x4 xs12[SM_NT], xs31[SM_NT];
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
-            vhalf[ct] = 0.0f;
-            pk[ct] = 0u;
-            all_ok[ct] = (task * per_iter + ct * 32 + 32) <= count;            // wave-uniform
+            vhalf[ct] = 0.0f; pk[ct] = 0u;
+            unsigned a12[4], a31[4];
+            split_parts(xo[ct], a12, a31);
+            xs12[ct] = u32x4{ a12[0], a12[1], a12[2], a12[3] };
+            xs31[ct] = u32x4{ a31[0], a31[1], a31[2], a31[3] };
         }
 #pragma unroll
         for (int T = 0; T < TILES; ++T) {
@@ -148,22 +188,38 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             for (int ct = 0; ct < SM_NT; ++ct)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
+            if constexpr (BF_LDS) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int s = 0; s < 3; ++s) bfrag[0][s] = bf_lds[(T * 3 + s) * 64 + lane];
+            }
+            const int TF = BF_LDS ? 0 : T;
+            // smallest part products first
 #pragma unroll
-                for (int ct = 0; ct < SM_NT; ++ct)
-                    acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfrag[T][s], xo[ct][s], acc[ct], 0, 0, 0);
+            for (int ct = 0; ct < SM_NT; ++ct)
+                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][2]),
+                                                                  __builtin_bit_cast(bf16x8, xs31[ct]), acc[ct], 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct)
+                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][1]),
+                                                                  __builtin_bit_cast(bf16x8, xs12[ct]), acc[ct], 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct)
+                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][0]),
+                                                                  __builtin_bit_cast(bf16x8, xs12[ct]), acc[ct], 0, 0, 0);
 
             // The asm blocks below read the accumulators, and the compiler's hazard handling does
             // not look into inline asm: no MFMA may sink below this point, and the wait states a
-            // vector read of a fresh sixteen-pass MFMA result needs (passes + 3 = 19) are explicit.
+            // vector read of a fresh MFMA result needs (at most passes + 3 = 19) are explicit.
+            // (the accumulators pass through the waiting block as operands, so that nothing that
+            // reads them can be scheduled above it)
             __builtin_amdgcn_sched_barrier(0);
-            asm volatile("s_nop 15\n\ts_nop 3");
+            static_assert(SM_NT == 2, "two accumulator tiles are named below");
+            asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
             float gm[SM_NT][2], l[SM_NT][2];
-            int idx[SM_NT][2];
-            bool single[SM_NT][2];      // wave-uniform: every lane has exactly one maximiser
-            auto leader = [&](int ct, int tl, int j) __attribute__((always_inline)) {
-                const lds_float *ra = rows_a[T][tl] + j * SM_AT_STRIDE;
+            unsigned idx[SM_NT][2];
+            unsigned n_eq = 0;          // wave-uniform: payoffs equal to their maximum, all four pairs
+            auto leader = [&](int ct, int tl, unsigned j) __attribute__((always_inline)) {
+                const lds_float *ra = rows_a[T][tl] + (int)j * SM_AT_STRIDE;
                 const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
                 const f32x4 qb = *(const __attribute__((address_space(3))) f32x4 *)(ra + oth_delta);
                 float v = xo[ct][0] * qa[0];
@@ -173,7 +229,6 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                 v = fmaf(xt[ct][3], qb[3], v);
                 return v;
             };
-            bool dirty = false;                                                   // wave-uniform
 #pragma unroll
             for (int ct = 0; ct < SM_NT; ++ct)
                 static_for<0, 2, 1>([&](auto tlc) {
@@ -182,35 +237,34 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                     m3 = vmax3(m3, acc[ct][8 * tl + 3], acc[ct][8 * tl + 4]);
                     m3 = vmax3(m3, acc[ct][8 * tl + 5], acc[ct][8 * tl + 6]);
                     gm[ct][tl] = vmax2(m3, acc[ct][8 * tl + 7]);
-                    unsigned ms = 0u;            // sum of (action + 2^16) over maximising registers
-                    match4(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2], acc[ct][8 * tl + 3],
-                           gm[ct][tl], 65536u, 65537u, 65538u, 65539u, ms);
-                    match4(acc[ct][8 * tl + 4], acc[ct][8 * tl + 5], acc[ct][8 * tl + 6], acc[ct][8 * tl + 7],
-                           gm[ct][tl], 65540u, 65541u, 65542u, 65543u, ms);
-                    idx[ct][tl] = (int)(ms & 7u);
-                    single[ct][tl] = __builtin_amdgcn_ballot_w64((ms >> 16) != 1u) == 0ull && all_ok[ct];
-                    dirty = dirty || !single[ct][tl];
+                    unsigned eq;
+                    argmax8(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2], acc[ct][8 * tl + 3],
+                            acc[ct][8 * tl + 4], acc[ct][8 * tl + 5], acc[ct][8 * tl + 6], acc[ct][8 * tl + 7],
+                            gm[ct][tl], idx[ct][tl], eq);
+                    n_eq += eq;
                 });
 #pragma unroll
             for (int ct = 0; ct < SM_NT; ++ct)
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl) l[ct][tl] = leader(ct, tl, idx[ct][tl]);
-            if (dirty) {
-                // exact: maximisers in ascending action order, leader payoff decides, then the
-                // lower action (lane-local; every lane owns its (candidate, type) pair)
+            if (n_eq != 4u * SM_NT * 32u) {
+                // Some lane has several maximisers (or none: a payoff that is not a number).
+                // Exact, for the four pairs of every lane: maximisers in ascending action order,
+                // leader payoff decides, then the lower action (lane-local; every lane owns its
+                // (candidate, type) pairs).  A lane with one maximiser gets what it had.
 #pragma unroll
                 for (int ct = 0; ct < SM_NT; ++ct)
                     static_for<0, 2, 1>([&](auto tlc) {
                         constexpr int tl = decltype(tlc)::value;
-                        if (single[ct][tl]) return;
-                        const bool ok = task * per_iter + ct * 32 + col < count;
+                        const bool ok = first + ct * 32 + col < count;
                         float lbest = 0.0f;
-                        int jbest = 0, nm = 0;
+                        unsigned jbest = 0;
+                        int nm = 0;
 #pragma unroll
                         for (int j = 0; j < SM_N; ++j)
                             if (acc[ct][8 * tl + j] == gm[ct][tl]) {
-                                const float lj = leader(ct, tl, j);
-                                if (nm == 0 || lj > lbest) { lbest = lj; jbest = j; }
+                                const float lj = leader(ct, tl, (unsigned)j);
+                                if (nm == 0 || lj > lbest) { lbest = lj; jbest = (unsigned)j; }
                                 ++nm;
                             }
                         l[ct][tl] = lbest; idx[ct][tl] = jbest;
@@ -222,25 +276,53 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl) {
                     vhalf[ct] = fmaf(prior[T][tl], l[ct][tl], vhalf[ct]);
-                    if (!EVAL) pk[ct] |= (unsigned)idx[ct][tl] << (3 * (2 * T + tl));
+                    if (!EVAL) pk[ct] |= idx[ct][tl] << (3 * (2 * T + tl));
                     if (EVAL) {
-                        const unsigned c = task * per_iter + ct * 32 + col;
-                        if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = idx[ct][tl];
+                        const unsigned c = first + ct * 32 + col;
+                        if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = (int32_t)idx[ct][tl];
                         if (a.l_out && c < count) a.l_out[(size_t)c * K + 4 * T + 2 * h + tl] = l[ct][tl];
                     }
                 }
         }
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
-            const unsigned c = task * per_iter + ct * 32 + col;
-            const bool ok = c < count;
+            const unsigned c = first + ct * 32 + col;
             float v = pair_sum(vhalf[ct]);
-            if (!(v == v)) v = -INFINITY;
             if (EVAL) {
-                if (a.V_out && ok && h == 0) a.V_out[c] = v;
-            } else if (ok && v > best_v) {           // a lane meets its candidates in ascending order
-                best_v = v; best_c = c; best_pk = pk[ct];
+                if (!(v == v)) v = -INFINITY;
+                if (a.V_out && c < count && h == 0) a.V_out[c] = v;
+            } else {
+                // a lane meets its candidates in ascending order: strictly greater replaces (a
+                // value that is not a number compares false and is never recorded, and neither
+                // is a row past the end of the range)
+                if (!full) v = c < count ? v : -INFINITY;
+                keep_greater(v, c, pk[ct], best_v, best_c, best_pk);
             }
+        }
+    };
+
+    if (GEN) {
+#pragma unroll 1
+        for (unsigned task = task0; task < n_tasks; task += task_stride) {
+            gen_task(task, own_a, oth_a);
+            process(task, task < n_full, own_a, oth_a);
+        }
+    } else {
+#pragma unroll 1
+        for (unsigned task = task0; task < n_full; task += 2 * task_stride) {
+            // (past the wavefront's last task the last whole task of the range is requested
+            // once more: one shape of loop body, and the waits for rows never depend on the
+            // position)
+            const unsigned next = task + task_stride, last = n_full - 1u;
+            load_task(next < last ? next : last, own_b, oth_b);
+            process(task, true, own_a, oth_a);
+            if (next >= n_full) break;
+            load_task(next + task_stride < last ? next + task_stride : last, own_a, oth_a);
+            process(next, true, own_b, oth_b);
+        }
+        if (n_full < n_tasks && n_full % task_stride == task0) {
+            load_ragged(n_full, own_a, oth_a);
+            process(n_full, false, own_a, oth_a);
         }
     }
 
@@ -293,7 +375,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 }
 
 template <int TILES, bool EVAL>
-__global__ void __launch_bounds__(SM_WAVES * 64, TILES <= 2 ? 4 : 3)
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 4 : 3)
 sweep_small_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, EVAL, false>(g, a, blockIdx.x, gridDim.x);
@@ -301,7 +383,7 @@ sweep_small_kernel(GameView g, SweepArgs a)
 
 // The sweep over rows generated in registers (step 1 fused in): no candidate ever reaches memory.
 template <int TILES>
-__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 5 : TILES == 2 ? 4 : 3)
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 4 : 3)
 sweep_small_gen_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, false, true>(g, a, blockIdx.x, gridDim.x);
@@ -413,8 +495,7 @@ hipError_t launch_sweep_small(const GameView &g, const SweepArgs &a, hipStream_t
     small_kernel_t k = a.gen ? small_gen_kernel_for(g.K) : small_kernel_for(g.K, eval);
     if (!k) return hipErrorNotSupported;
     if (!a.gen && ((uintptr_t)a.X & 15) != 0) return hipErrorInvalidValue;   // the API layer checks alignment
-    // (the generating kernel of a four-type game fits five workgroups per compute unit)
-    const int per_cu = a.gen && g.K == 4 ? 5 : 4;
+    const int per_cu = 4;
     hipLaunchKernelGGL(k, dim3((unsigned)small_blocks(a.count, per_cu)), dim3(SM_WAVES * 64), 0, s, g, a);
     return hipGetLastError();
 }
@@ -427,29 +508,57 @@ hipError_t launch_finish_small(const GameView &g, const FinishArgs &f, hipStream
     return hipGetLastError();
 }
 
+// fp32 -> nearest bf16 (ties to even), as the 16 high bits; and back.
+static inline unsigned short bf16_rne_bits(float f)
+{
+    unsigned u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+static inline float bf16_bits_to_float(unsigned short b)
+{
+    const unsigned u = (unsigned)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
 // Host packing for the small-game kernel.
-// Bpack: [tile][k-step s][lane] fp32; lane = 32*kh + i supplies B_t[k = 4*kh + s][j] for tile
-// row i = 8q + 4hh + rr, which stands for type t = 4*tile + 2*hh + q/2, action j = 4*(q%2) + rr.
+// Bpack: [tile][instruction i][lane][8] bf16; lane = 32*kh + r supplies, for tile row r = 8q +
+// 4hh + rr (type t = 4*tile + 2*hh + q/2, action j = 4*(q%2) + rr), element e: the part of
+// B_t[k = 4*kh + e%4][j] that instruction i multiplies in that slot: (b1, b1), (b2, b2), (b1, b3)
+// for (e < 4, e >= 4) and i = 0, 1, 2, where b = b1 + b2 + b3 in bf16 parts.
 // ATpack: [type][action][12] fp32: the leader column of (type, action) over the m leader
 // actions, zero padded to 8, then 4 floats of padding.
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes)
 {
     const int tiles = K / 4;
-    *Bbytes = (size_t)tiles * 4 * 64 * sizeof(float);
+    *Bbytes = (size_t)tiles * 3 * 64 * 8 * sizeof(unsigned short);
     *ATbytes = (size_t)K * SM_N * SM_AT_STRIDE * sizeof(float);
-    float *pb = (float *)calloc(*Bbytes, 1);
+    unsigned short *pb = (unsigned short *)calloc(*Bbytes, 1);
     float *pa = (float *)calloc(*ATbytes, 1);
     *Bpack = pb; *ATpack = pa;
     if (!pb || !pa) { free(pb); free(pa); *Bpack = nullptr; *ATpack = nullptr; return; }
+    static const int part_of[3][2] = { { 0, 0 }, { 1, 1 }, { 0, 2 } };
     for (int T = 0; T < tiles; ++T)
-        for (int s = 0; s < 4; ++s)
-            for (int lane = 0; lane < 64; ++lane) {
-                const int kh = lane / 32, i = lane % 32;
-                const int q = i / 8, hh = (i % 8) / 4, rr = i % 4;
-                const int t = 4 * T + 2 * hh + q / 2, j = 4 * (q % 2) + rr, k = 4 * kh + s;
-                pb[(T * 4 + s) * 64 + lane] = k < m ? B[((size_t)t * m + k) * n + j] : 0.0f;
+        for (int lane = 0; lane < 64; ++lane) {
+            const int kh = lane / 32, r = lane % 32;
+            const int q = r / 8, hh = (r % 8) / 4, rr = r % 4;
+            const int t = 4 * T + 2 * hh + q / 2, j = 4 * (q % 2) + rr;
+            for (int e = 0; e < 8; ++e) {
+                const int k = 4 * kh + e % 4;
+                const float b = k < m ? B[((size_t)t * m + k) * n + j] : 0.0f;
+                unsigned short part[3];
+                part[0] = bf16_rne_bits(b);
+                const float r1 = b - bf16_bits_to_float(part[0]);
+                part[1] = bf16_rne_bits(r1);
+                part[2] = bf16_rne_bits(r1 - bf16_bits_to_float(part[1]));
+                for (int i = 0; i < 3; ++i)
+                    pb[(((size_t)T * 3 + i) * 64 + lane) * 8 + e] = part[part_of[i][e / 4]];
             }
+        }
     for (int t = 0; t < K; ++t)
         for (int j = 0; j < n; ++j)
             for (int i = 0; i < m; ++i)
