@@ -31,7 +31,11 @@ extern "C" const char *bsse_last_error(void) { return g_err; }
 
 extern "C" const char *bsse_status_name(bsse_status s)
 {
-    switch (s) {
+    // (a C caller can hand over any integer: read it as one)
+    int code;
+    memcpy(&code, &s, sizeof(code));
+    static_assert(sizeof(code) == sizeof(s), "status codes are ints");
+    switch (code) {
     case BSSE_OK: return "BSSE_OK";
     case BSSE_EINVAL: return "BSSE_EINVAL";
     case BSSE_ENOTFINITE: return "BSSE_ENOTFINITE";
