@@ -184,6 +184,76 @@ __device__ __forceinline__ void argmax8(float u0, float u1, float u2, float u3, 
     idx = i; n_eq = c;
 }
 
+// Eight follower payoffs u with their maximum g, and the eight leader payoffs w beside them:
+// l = w at the lowest position where u holds g; n_eq = how many (lane, position) pairs of the
+// wavefront hold g (64 exactly when every lane has one maximiser); with WANT_IDX also that
+// position.  Compare masks in scalar pairs, selects from the highest position down, the count on
+// the scalar unit, every select at least two instructions behind its compare.
+template <bool WANT_IDX>
+__device__ __forceinline__ void argmax8_pick(const float (&u)[8], const float (&w)[8], float g, float &l,
+                                             unsigned &idx, unsigned &n_eq)
+{
+    unsigned long long m0, m1, m2, m3, m4, m5, m6, m7;
+    unsigned c, t;
+    float lv;
+    asm("v_cmp_eq_f32 %[m6], %[u6], %[g]\n\t"
+        "v_cmp_eq_f32 %[m5], %[u5], %[g]\n\t"
+        "v_cmp_eq_f32 %[m4], %[u4], %[g]\n\t"
+        "v_cmp_eq_f32 %[m3], %[u3], %[g]\n\t"
+        "v_cmp_eq_f32 %[m2], %[u2], %[g]\n\t"
+        "v_cmp_eq_f32 %[m1], %[u1], %[g]\n\t"
+        "v_cmp_eq_f32 %[m0], %[u0], %[g]\n\t"
+        "v_cmp_eq_f32 %[m7], %[u7], %[g]\n\t"
+        "v_cndmask_b32 %[l], %[w7], %[w6], %[m6]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w5], %[m5]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w4], %[m4]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w3], %[m3]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w2], %[m2]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w1], %[m1]\n\t"
+        "v_cndmask_b32 %[l], %[l], %[w0], %[m0]\n\t"
+        "s_bcnt1_i32_b64 %[c], %[m0]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m1]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m2]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m3]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m4]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m5]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m6]\n\t"
+        "s_add_u32 %[c], %[c], %[t]\n\t"
+        "s_bcnt1_i32_b64 %[t], %[m7]\n\t"
+        "s_add_u32 %[c], %[c], %[t]"
+        : [l] "=&v"(lv), [c] "=&s"(c), [t] "=&s"(t), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2),
+          [m3] "=&s"(m3), [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6), [m7] "=&s"(m7)
+        : [u0] "v"(u[0]), [u1] "v"(u[1]), [u2] "v"(u[2]), [u3] "v"(u[3]), [u4] "v"(u[4]), [u5] "v"(u[5]),
+          [u6] "v"(u[6]), [u7] "v"(u[7]), [w0] "v"(w[0]), [w1] "v"(w[1]), [w2] "v"(w[2]), [w3] "v"(w[3]),
+          [w4] "v"(w[4]), [w5] "v"(w[5]), [w6] "v"(w[6]), [w7] "v"(w[7]), [g] "v"(g)
+        : "scc");
+    l = lv; n_eq = c;
+    if constexpr (WANT_IDX) {
+        // (evaluation mode only: the position itself, by the same rule)
+        unsigned i = 7u;
+#pragma unroll
+        for (int j = 6; j >= 0; --j) i = u[j] == g ? (unsigned)j : i;
+        idx = i;
+    }
+}
+
+// (bv, bc) <- (v, c) in the lanes where v > bv; the mask in a scalar register pair.
+__device__ __forceinline__ void keep_greater2(float v, unsigned c, float &bv, unsigned &bc)
+{
+    unsigned long long m;
+    asm("v_cmp_gt_f32 %[m], %[v], %[bv]\n\t"
+        "s_nop 1\n\t"
+        "v_cndmask_b32 %[bv], %[bv], %[v], %[m]\n\t"
+        "v_cndmask_b32 %[bc], %[bc], %[c], %[m]"
+        : [bv] "+v"(bv), [bc] "+v"(bc), [m] "=&s"(m)
+        : [v] "v"(v), [c] "v"(c));
+}
+
 // (bv, bc, bp) <- (v, c, p) in the lanes where v > bv; the mask in a scalar register pair.
 __device__ __forceinline__ void keep_greater(float v, unsigned c, unsigned p, float &bv, unsigned &bc,
                                              unsigned &bp)

@@ -19,10 +19,12 @@
 // x2 b2, x3 b1, x1 b3; the others are below 2^-25 of the product -- fill the 48 k-slots of
 // three 32x32x16 instructions (3 cycles per candidate, beside the vector unit, not in it).
 // Slot order: instruction i, lane half kh, element e: part P_i (e < 4) or Q_i (e >= 4) of
-// leader action 4 kh + (e % 4), so that a lane splits only the four components it already
-// holds for the leader payoff.  The follower parts are split on the host and stay in
-// registers for the kernel's life; the leader matrix sits in LDS, one padded row per (type,
-// action), in fp32.
+// leader action 4 kh + (e % 4), so that a lane splits only the four components of its own lane
+// half.  The leader payoffs of all eight actions of a (candidate, type) pair come off the matrix
+// pipe the same way (three more instructions per tile, against the leader matrix in the same
+// packing): the value at the best response is then a chain of selects under the masks of the
+// arg-max compares, and nothing in the loop touches LDS or reads the other half of the row.
+// Both matrices' parts are split on the host and stay in registers for the kernel's life.
 #include "bsse_internal.h"
 #include "mfma_device.h"
 #include "gen_device.h"
@@ -41,8 +43,25 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int SM_M = 8, SM_N = 8;
 constexpr int SM_WAVES = 4;
 constexpr int SM_NT = 2;               // 32-candidate tiles per wavefront per iteration
-constexpr int SM_AT_STRIDE = 12;       // floats per leader row in LDS (8 + pad: bank spread)
 constexpr int SM_MAX_TILES = 4;
+#ifndef BSSE_SM_RING
+#define BSSE_SM_RING 2
+#endif
+constexpr int SM_RING = BSSE_SM_RING;    // sets of row registers of the sweep over a buffer
+
+// A 16-byte global load issued by hand (wave-uniform base, 32-bit lane offset, immediate offset)
+// and the wait that makes the registers of two such loads usable: "at most PENDING vector memory
+// operations outstanding", with the loaded values as operands so that nothing that uses them can
+// be scheduled above the wait.  The compiler neither sees these loads nor waits for them: its own
+// waits for rows in flight around a loop were "nothing outstanding" at the top of every trip.
+template <int OFFSET> __device__ __forceinline__ void row_request(f32x4 &dst, unsigned lane_offset, const void *base)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(lane_offset), "s"(base), "n"(OFFSET));
+}
+template <int PENDING> __device__ __forceinline__ void rows_await(f32x4 &a, f32x4 &b)
+{
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(PENDING));
+}
 
 // TILES = K / 4 row tiles.  EVAL: per-candidate outputs instead of the workgroup record.
 // Requires m == 8 and 16-byte aligned candidate rows (checked by the launcher).  The body of a
@@ -51,10 +70,8 @@ template <int TILES, bool EVAL, bool GEN>
 __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a, unsigned block,
                                            unsigned nblocks)
 {
-    __shared__ __attribute__((aligned(16))) float at_lds[TILES * 4 * SM_N * SM_AT_STRIDE];
     __shared__ float red_v[SM_WAVES];
     __shared__ unsigned red_c[SM_WAVES];
-    __shared__ unsigned red_p[SM_WAVES][2];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -67,41 +84,36 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     const unsigned task0 = block * SM_WAVES + wave;
     const unsigned task_stride = nblocks * SM_WAVES;
 
-    // candidate rows of one task: own = x[4h..4h+3] (the MFMA k-slots of this lane half),
-    // oth = the other four components (needed for the leader payoff only).  Two sets of row
-    // registers take turns: while one task is worked on, the rows of the wavefront's next task
-    // land in the other set.  A task that lies wholly inside the range is addressed as a
-    // wave-uniform base plus a fixed lane offset (no vector address arithmetic); the one ragged
-    // task at the end of the range is done after the loop by the wavefront whose turn it is,
-    // with the rows past the end reading the last row instead: they are evaluated like any
-    // other and then left out of every result.
+    // candidate rows of one task: a lane holds x[4h..4h+3] of its candidate, the MFMA k-slots of
+    // its lane half (the partner lane holds the other four; nothing else needs them).  Two sets of
+    // row registers take turns: while one task is worked on, the rows of the wavefront's next
+    // task land in the other set.  A task that lies wholly inside the range is addressed as a
+    // wave-uniform base plus a fixed lane offset; the one ragged task at the end of the range is
+    // done after the loop by the wavefront whose turn it is, with the rows past the end reading
+    // the last row instead: they are evaluated like any other and then left out of every result.
     const unsigned lane_own = (unsigned)(col * SM_M + 4 * h) * 4u;
-    const unsigned lane_oth = (unsigned)(col * SM_M + 4 * (1 - h)) * 4u;
-    auto load_task = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
-        const char *base = reinterpret_cast<const char *>(a.X) + (size_t)task * (per_iter * SM_M * 4);
-#pragma unroll
-        for (int ct = 0; ct < SM_NT; ++ct) {
-            own[ct] = *(const f32x4 *)(base + ct * 32 * SM_M * 4 + lane_own);
-            oth[ct] = *(const f32x4 *)(base + ct * 32 * SM_M * 4 + lane_oth);
-        }
+    auto load_task = [&](unsigned task, f32x4 (&own)[SM_NT]) __attribute__((always_inline)) {
+        // (the task index is the same in every lane; said so, the base stays in scalar registers)
+        const unsigned utask = (unsigned)__builtin_amdgcn_readfirstlane((int)task);
+        const char *base = reinterpret_cast<const char *>(a.X) + (size_t)utask * (per_iter * SM_M * 4);
+        static_assert(SM_NT == 2, "two tiles of rows are requested below");
+        row_request<0>(own[0], lane_own, base);
+        row_request<32 * SM_M * 4>(own[1], lane_own, base);
     };
-    auto load_ragged = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
+    auto load_ragged = [&](unsigned task, f32x4 (&own)[SM_NT]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
             unsigned c = task * per_iter + ct * 32 + col;
             c = c < count ? c : count - 1u;
-            const float *row = a.X + (size_t)c * SM_M;
-            own[ct] = *(const f32x4 *)(row + 4 * h);
-            oth[ct] = *(const f32x4 *)(row + 4 * (1 - h));
+            own[ct] = *(const f32x4 *)(a.X + (size_t)c * SM_M + 4 * h);
         }
     };
     const unsigned n_full = count / per_iter;            // tasks wholly inside the range
     // GEN: the rows are made here instead.  Lane half h produces components 4h..4h+3 of its
-    // candidate (the thread (row, b = h) of the generation kernel); the row sum and the other four
-    // components come from the partner lane.  Rows past the end of the range are ordinary rows of
-    // the generator; they are left out of every result.
-    const int partner_addr = 4 * (lane ^ 32);
-    auto gen_task = [&](unsigned task, f32x4 (&own)[SM_NT], f32x4 (&oth)[SM_NT]) __attribute__((always_inline)) {
+    // candidate (the thread (row, b = h) of the generation kernel); the row sum comes from the
+    // pair.  Rows past the end of the range are ordinary rows of the generator; they are left out
+    // of every result.
+    auto gen_task = [&](unsigned task, f32x4 (&own)[SM_NT]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
             const unsigned c = task * per_iter + ct * 32 + col;
@@ -110,46 +122,38 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             const float sum = pair_sum(dirichlet_quad_sum(g0, g1, g2, g3));
             dirichlet_quad_scale(sum, SM_M, g0, g1, g2, g3);
             own[ct] = f32x4{ g0, g1, g2, g3 };
-#pragma unroll
-            for (int k = 0; k < 4; ++k) oth[ct][k] = pair_other(own[ct][k], partner_addr);
         }
     };
-    f32x4 own_a[SM_NT], oth_a[SM_NT], own_b[SM_NT], oth_b[SM_NT];
-    if (!GEN && task0 < n_full) load_task(task0, own_a, oth_a);       // first rows in flight during set-up
+    f32x4 ring[SM_RING][SM_NT];
+    f32x4 (&own_a)[SM_NT] = ring[0];
+    if (!GEN && task0 < n_full) load_task(task0, ring[0]);           // first rows in flight during set-up
 
-    // leader rows -> LDS (packed on the host with the padded stride); follower fragments and
-    // priors -> registers
-    {
-        const float *src = reinterpret_cast<const float *>(g.ATpack);
-        for (int e = tid; e < TILES * 4 * SM_N * SM_AT_STRIDE; e += SM_WAVES * 64) at_lds[e] = src[e];
-    }
-    // per instruction: eight bf16 k-slots of this lane's tile row.  One row tile's fragments live
-    // in registers for the kernel's life; with more tiles they are re-read from LDS at every
-    // tile (registers for all of them cost spills in the loop).
-    constexpr bool BF_LDS = TILES >= 2;
-    __shared__ __attribute__((aligned(16))) u32x4 bf_lds[BF_LDS ? TILES * 3 * 64 : 1];
-    u32x4 bfrag[BF_LDS ? 1 : TILES][3];
+    // per instruction: eight bf16 k-slots of this lane's tile row, follower payoffs (bfrag) and
+    // leader payoffs (afrag) alike.  One row tile's fragments live in registers for the kernel's
+    // life; with more tiles they are re-read from LDS at every tile (registers for all of them
+    // cost spills in the loop).
+    constexpr bool FR_LDS = TILES >= 2;
+    __shared__ __attribute__((aligned(16))) u32x4 fr_lds[FR_LDS ? 2 * TILES * 3 * 64 : 1];
+    u32x4 bfrag[FR_LDS ? 1 : TILES][3], afrag[FR_LDS ? 1 : TILES][3];
     float prior[TILES][2];
-    const lds_float *rows_a[TILES][2];  // this lane's (type) leader rows, own-half columns
-    int oth_delta;                      // float offset from own-half to other-half columns
-    const lds_float *at_l = (const lds_float *)at_lds;
     {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(g.Bpack);
+        const u32x4 *srcb = reinterpret_cast<const u32x4 *>(g.Bpack);
+        const u32x4 *srca = reinterpret_cast<const u32x4 *>(g.ATpack);
 #pragma unroll
         for (int T = 0; T < TILES; ++T) {
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                if constexpr (BF_LDS) { if (wave == 0) bf_lds[(T * 3 + s) * 64 + lane] = src[(T * 3 + s) * 64 + lane]; }
-                else bfrag[T][s] = src[(T * 3 + s) * 64 + lane];
+                if constexpr (FR_LDS) {
+                    if (wave == 0) fr_lds[(T * 3 + s) * 64 + lane] = srcb[(T * 3 + s) * 64 + lane];
+                    if (wave == 1) fr_lds[((TILES + T) * 3 + s) * 64 + lane] = srca[(T * 3 + s) * 64 + lane];
+                } else {
+                    bfrag[T][s] = srcb[(T * 3 + s) * 64 + lane];
+                    afrag[T][s] = srca[(T * 3 + s) * 64 + lane];
+                }
             }
 #pragma unroll
-            for (int tl = 0; tl < 2; ++tl) {
-                const int t = 4 * T + 2 * h + tl;
-                prior[T][tl] = g.prior[t];
-                rows_a[T][tl] = at_l + t * SM_N * SM_AT_STRIDE + 4 * h;
-            }
+            for (int tl = 0; tl < 2; ++tl) prior[T][tl] = g.prior[4 * T + 2 * h + tl];
         }
-        oth_delta = 4 * (1 - h) - 4 * h;
     }
     // every set-up load has landed before the loop: the compiler would otherwise place its
     // waits for them at their first use, inside the loop, where they also wait for row requests
@@ -158,24 +162,20 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 
     float best_v = -INFINITY;
     unsigned best_c = 0xFFFFFFFFu;
-    // best responses of the lane's best candidate, three bits each: this lane half's types only,
-    // type 4T + 2h + tl at bits 3(2T + tl)
-    unsigned best_pk = 0u;
     unsigned tie_count = 0;
 
     // One task: both candidate tiles and both of the lane's types advance together through one
     // straight-line block (four independent dependency chains for the scheduler to interleave);
     // the exact tie routine is a single rare branch per row tile.
-    auto process = [&](unsigned task, bool full, const f32x4 (&xo)[SM_NT], const f32x4 (&xt)[SM_NT]) __attribute__((always_inline)) {
+    auto process = [&](unsigned task, bool full, const f32x4 (&xo)[SM_NT]) __attribute__((always_inline)) {
         const unsigned first = task * per_iter;
         float vhalf[SM_NT];
-        unsigned pk[SM_NT];
         // the lane's four components as three bf16 parts: k-slots (x1, x2) for the instructions
-        // against b1 and b2, (x3, x1) for the one against (b1, b3)
+        // against the first and second payoff parts, (x3, x1) for the one against (first, third)
         u32x4 xs12[SM_NT], xs31[SM_NT];
 #pragma unroll
         for (int ct = 0; ct < SM_NT; ++ct) {
-            vhalf[ct] = 0.0f; pk[ct] = 0u;
+            vhalf[ct] = 0.0f;
             unsigned a12[4], a31[4];
             split_parts(xo[ct], a12, a31);
             xs12[ct] = u32x4{ a12[0], a12[1], a12[2], a12[3] };
@@ -183,29 +183,36 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         }
 #pragma unroll
         for (int T = 0; T < TILES; ++T) {
-            f32x16 acc[SM_NT];
+            if constexpr (FR_LDS) {
 #pragma unroll
-            for (int ct = 0; ct < SM_NT; ++ct)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[ct][r] = 0.0f;
-            if constexpr (BF_LDS) {
-#pragma unroll
-                for (int s = 0; s < 3; ++s) bfrag[0][s] = bf_lds[(T * 3 + s) * 64 + lane];
+                for (int s = 0; s < 3; ++s) {
+                    bfrag[0][s] = fr_lds[(T * 3 + s) * 64 + lane];
+                    afrag[0][s] = fr_lds[((TILES + T) * 3 + s) * 64 + lane];
+                }
             }
-            const int TF = BF_LDS ? 0 : T;
-            // smallest part products first
+            const int TF = FR_LDS ? 0 : T;
+            // follower payoffs u and leader payoffs w of the tile's 32 (type, action) rows, smallest
+            // part products first
+            f32x16 u[SM_NT], w[SM_NT];
 #pragma unroll
             for (int ct = 0; ct < SM_NT; ++ct)
-                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][2]),
-                                                                  __builtin_bit_cast(bf16x8, xs31[ct]), acc[ct], 0, 0, 0);
 #pragma unroll
-            for (int ct = 0; ct < SM_NT; ++ct)
-                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][1]),
-                                                                  __builtin_bit_cast(bf16x8, xs12[ct]), acc[ct], 0, 0, 0);
+                for (int r = 0; r < 16; ++r) { u[ct][r] = 0.0f; w[ct][r] = 0.0f; }
+            auto mm = [](const u32x4 &fr, const u32x4 &xs, const f32x16 &c) __attribute__((always_inline)) {
+                return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr), __builtin_bit_cast(bf16x8, xs), c, 0, 0, 0);
+            };
 #pragma unroll
-            for (int ct = 0; ct < SM_NT; ++ct)
-                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[TF][0]),
-                                                                  __builtin_bit_cast(bf16x8, xs12[ct]), acc[ct], 0, 0, 0);
+            for (int ct = 0; ct < SM_NT; ++ct) u[ct] = mm(bfrag[TF][2], xs31[ct], u[ct]);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct) u[ct] = mm(bfrag[TF][1], xs12[ct], u[ct]);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct) u[ct] = mm(bfrag[TF][0], xs12[ct], u[ct]);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct) w[ct] = mm(afrag[TF][2], xs31[ct], w[ct]);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct) w[ct] = mm(afrag[TF][1], xs12[ct], w[ct]);
+#pragma unroll
+            for (int ct = 0; ct < SM_NT; ++ct) w[ct] = mm(afrag[TF][0], xs12[ct], w[ct]);
 
             // The asm blocks below read the accumulators, and the compiler's hazard handling does
             // not look into inline asm: no MFMA may sink below this point, and the wait states a
@@ -213,40 +220,28 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
             // (the accumulators pass through the waiting block as operands, so that nothing that
             // reads them can be scheduled above it)
             __builtin_amdgcn_sched_barrier(0);
-            static_assert(SM_NT == 2, "two accumulator tiles are named below");
-            asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
+            static_assert(SM_NT == 2, "two pairs of accumulator tiles are named below");
+            asm volatile("s_nop 15\n\ts_nop 3" : "+v"(u[0]), "+v"(u[1]), "+v"(w[0]), "+v"(w[1]));
             float gm[SM_NT][2], l[SM_NT][2];
             unsigned idx[SM_NT][2];
             unsigned n_eq = 0;          // wave-uniform: payoffs equal to their maximum, all four pairs
-            auto leader = [&](int ct, int tl, unsigned j) __attribute__((always_inline)) {
-                const lds_float *ra = rows_a[T][tl] + (int)j * SM_AT_STRIDE;
-                const f32x4 qa = *(const __attribute__((address_space(3))) f32x4 *)ra;
-                const f32x4 qb = *(const __attribute__((address_space(3))) f32x4 *)(ra + oth_delta);
-                float v = xo[ct][0] * qa[0];
-                v = fmaf(xo[ct][1], qa[1], v); v = fmaf(xo[ct][2], qa[2], v);
-                v = fmaf(xo[ct][3], qa[3], v); v = fmaf(xt[ct][0], qb[0], v);
-                v = fmaf(xt[ct][1], qb[1], v); v = fmaf(xt[ct][2], qb[2], v);
-                v = fmaf(xt[ct][3], qb[3], v);
-                return v;
-            };
 #pragma unroll
             for (int ct = 0; ct < SM_NT; ++ct)
                 static_for<0, 2, 1>([&](auto tlc) {
                     constexpr int tl = decltype(tlc)::value;
-                    float m3 = vmax3(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2]);
-                    m3 = vmax3(m3, acc[ct][8 * tl + 3], acc[ct][8 * tl + 4]);
-                    m3 = vmax3(m3, acc[ct][8 * tl + 5], acc[ct][8 * tl + 6]);
-                    gm[ct][tl] = vmax2(m3, acc[ct][8 * tl + 7]);
+                    float m3 = vmax3(u[ct][8 * tl], u[ct][8 * tl + 1], u[ct][8 * tl + 2]);
+                    m3 = vmax3(m3, u[ct][8 * tl + 3], u[ct][8 * tl + 4]);
+                    m3 = vmax3(m3, u[ct][8 * tl + 5], u[ct][8 * tl + 6]);
+                    gm[ct][tl] = vmax2(m3, u[ct][8 * tl + 7]);
                     unsigned eq;
-                    argmax8(acc[ct][8 * tl], acc[ct][8 * tl + 1], acc[ct][8 * tl + 2], acc[ct][8 * tl + 3],
-                            acc[ct][8 * tl + 4], acc[ct][8 * tl + 5], acc[ct][8 * tl + 6], acc[ct][8 * tl + 7],
-                            gm[ct][tl], idx[ct][tl], eq);
+                    float uu[8], ww[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) { uu[j] = u[ct][8 * tl + j]; ww[j] = w[ct][8 * tl + j]; }
+                    idx[ct][tl] = 0u;
+                    if (EVAL) argmax8_pick<true>(uu, ww, gm[ct][tl], l[ct][tl], idx[ct][tl], eq);
+                    else argmax8_pick<false>(uu, ww, gm[ct][tl], l[ct][tl], idx[ct][tl], eq);
                     n_eq += eq;
                 });
-#pragma unroll
-            for (int ct = 0; ct < SM_NT; ++ct)
-#pragma unroll
-                for (int tl = 0; tl < 2; ++tl) l[ct][tl] = leader(ct, tl, idx[ct][tl]);
             if (n_eq != 4u * SM_NT * 32u) {
                 // Some lane has several maximisers (or none: a payoff that is not a number).
                 // Exact, for the four pairs of every lane: maximisers in ascending action order,
@@ -262,8 +257,8 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                         int nm = 0;
 #pragma unroll
                         for (int j = 0; j < SM_N; ++j)
-                            if (acc[ct][8 * tl + j] == gm[ct][tl]) {
-                                const float lj = leader(ct, tl, (unsigned)j);
+                            if (u[ct][8 * tl + j] == gm[ct][tl]) {
+                                const float lj = w[ct][8 * tl + j];
                                 if (nm == 0 || lj > lbest) { lbest = lj; jbest = (unsigned)j; }
                                 ++nm;
                             }
@@ -276,7 +271,6 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 #pragma unroll
                 for (int tl = 0; tl < 2; ++tl) {
                     vhalf[ct] = fmaf(prior[T][tl], l[ct][tl], vhalf[ct]);
-                    if (!EVAL) pk[ct] |= idx[ct][tl] << (3 * (2 * T + tl));
                     if (EVAL) {
                         const unsigned c = first + ct * 32 + col;
                         if (a.br_out && c < count) a.br_out[(size_t)c * K + 4 * T + 2 * h + tl] = (int32_t)idx[ct][tl];
@@ -296,7 +290,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
                 // value that is not a number compares false and is never recorded, and neither
                 // is a row past the end of the range)
                 if (!full) v = c < count ? v : -INFINITY;
-                keep_greater(v, c, pk[ct], best_v, best_c, best_pk);
+                keep_greater2(v, c, best_v, best_c);
             }
         }
     };
@@ -304,25 +298,46 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
     if (GEN) {
 #pragma unroll 1
         for (unsigned task = task0; task < n_tasks; task += task_stride) {
-            gen_task(task, own_a, oth_a);
-            process(task, task < n_full, own_a, oth_a);
+            gen_task(task, own_a);
+            process(task, task < n_full, own_a);
         }
     } else {
-#pragma unroll 1
-        for (unsigned task = task0; task < n_full; task += 2 * task_stride) {
-            // (past the wavefront's last task the last whole task of the range is requested
-            // once more: one shape of loop body, and the waits for rows never depend on the
-            // position)
-            const unsigned next = task + task_stride, last = n_full - 1u;
-            load_task(next < last ? next : last, own_b, oth_b);
-            process(task, true, own_a, oth_a);
-            if (next >= n_full) break;
-            load_task(next + task_stride < last ? next + task_stride : last, own_a, oth_a);
-            process(next, true, own_b, oth_b);
+        // SM_RING sets of row registers: the rows of the wavefront's next SM_RING - 1 tasks are in
+        // flight while one task is worked on (with one task in flight the loop was bound by the
+        // latency of its loads, not by their bandwidth).  Past the wavefront's last task the last
+        // whole task of the range is requested again: one shape of loop body, and the waits for
+        // rows never depend on the position.
+        const unsigned last = n_full > 0 ? n_full - 1u : 0u;
+        auto request = [&](unsigned task, f32x4 (&own)[SM_NT]) __attribute__((always_inline)) {
+            load_task(task < last ? task : last, own);
+        };
+        if (task0 < n_full) {
+            static_for<1, SM_RING - 1, 1>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                request(task0 + q * task_stride, ring[q]);
+            });
         }
+#pragma unroll 1
+        for (unsigned task = task0; task < n_full; task += SM_RING * task_stride) {
+            bool done = false;
+            static_for<0, SM_RING, 1>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                if (done) return;
+                const unsigned mine = task + q * task_stride;
+                if (mine >= n_full) { done = true; return; }
+                request(mine + (SM_RING - 1) * task_stride, ring[(q + SM_RING - 1) % SM_RING]);
+                // the SM_RING - 1 later tasks' loads (two each, issued in order) may stay in flight;
+                // in evaluation mode stores are in flight as well, and everything is waited for
+                rows_await<EVAL ? 0 : 2 * (SM_RING - 1)>(ring[q][0], ring[q][1]);
+                process(mine, true, ring[q]);
+            });
+            if (done) break;
+        }
+        // nothing may still be on its way into registers that are about to mean something else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (n_full < n_tasks && n_full % task_stride == task0) {
-            load_ragged(n_full, own_a, oth_a);
-            process(n_full, false, own_a, oth_a);
+            load_ragged(n_full, own_a);
+            process(n_full, false, own_a);
         }
     }
 
@@ -331,28 +346,25 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
         for (int d = 16; d >= 1; d >>= 1) {          // both lane halves hold the same values
             const float ov = __shfl_xor(best_v, d, 64);
             const unsigned oc = __shfl_xor(best_c, d, 64);
-            const unsigned op = __shfl_xor(best_pk, d, 64);
-            if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; best_pk = op; }
+            if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; }
         }
-        // lanes 0 and 32 now hold the same candidate, each with its half of the best responses
-        if (lane == 0) { red_v[wave] = best_v; red_c[wave] = best_c; red_p[wave][0] = best_pk; }
-        if (lane == 32) red_p[wave][1] = best_pk;
+        if (lane == 0) { red_v[wave] = best_v; red_c[wave] = best_c; }
         __syncthreads();
         if (tid == 0) {
-            int bw = 0;
-            for (int w = 1; w < SM_WAVES; ++w)
-                if (red_v[w] > best_v || (red_v[w] == best_v && red_c[w] < best_c)) {
-                    best_v = red_v[w]; best_c = red_c[w]; bw = w;
+            for (int w2 = 1; w2 < SM_WAVES; ++w2)
+                if (red_v[w2] > best_v || (red_v[w2] == best_v && red_c[w2] < best_c)) {
+                    best_v = red_v[w2]; best_c = red_c[w2];
                 }
             // step 6: the workgroup's own running best over the chunks of this sweep (greater
-            // value, then lower global index); nobody else touches the slot
+            // value, then lower global index); nobody else touches the slot.  The slot keeps the
+            // row; the best responses of the sweep's winner are found at the end, by evaluating
+            // that one row again.
             SmallSlot *slot = a.small.slots + block;
             const long long gi = a.index_base + (long long)best_c;
             if (best_c != 0xFFFFFFFFu &&
                 (slot->epoch != a.small.epoch || best_v > slot->value ||
                  (best_v == slot->value && gi < slot->index))) {
                 slot->value = best_v; slot->epoch = a.small.epoch; slot->index = gi;
-                slot->br[0] = red_p[bw][0]; slot->br[1] = red_p[bw][1];
                 if (GEN) {
                     float q[SM_M];
                     const long long row = a.gen_first + (long long)best_c;
@@ -375,7 +387,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 }
 
 template <int TILES, bool EVAL>
-__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 4 : 3)
+__global__ void __launch_bounds__(SM_WAVES * 64, 3)
 sweep_small_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, EVAL, false>(g, a, blockIdx.x, gridDim.x);
@@ -390,8 +402,9 @@ sweep_small_gen_kernel(GameView g, SweepArgs a)
 }
 
 // Steps 5-6 at the end of a sweep: fold the slots of the current sweep (greatest value, lowest
-// index among equals) and report the winner: value, index, tie count, row and best responses
-// (unpacked from the slot; nothing is evaluated again).
+// index among equals) and report the winner: value, index, tie count and row.  Its best
+// responses come from a one-row evaluation launch behind this kernel (launch_finish_small): the
+// same instruction sequence on the same row, hence the same decisions.
 __global__ void __launch_bounds__(SM_WAVES * 64)
 small_finish_kernel(int K, FinishArgs f)
 {
@@ -433,12 +446,6 @@ small_finish_kernel(int K, FinishArgs f)
     *f.run_host = r;
     if (bb < 0) return;
     *f.win_v = bv;
-    const unsigned p0 = f.slots[bb].br[0], p1 = f.slots[bb].br[1];
-    for (int p = 0; 2 * p < K; ++p) {
-        const int t = 4 * (p >> 1) + (p & 1);
-        f.win_br[t] = (int32_t)((p0 >> (3 * p)) & 7u);          // lane half 0: types 4T, 4T+1
-        f.win_br[t + 2] = (int32_t)((p1 >> (3 * p)) & 7u);      // lane half 1: types 4T+2, 4T+3
-    }
     for (int i = 0; i < SM_M; ++i) f.best_x[i] = f.slots[bb].x[i];
 }
 
@@ -505,6 +512,16 @@ int small_num_slots() { return 256 * 5; }          // the largest grid launch_sw
 hipError_t launch_finish_small(const GameView &g, const FinishArgs &f, hipStream_t s)
 {
     hipLaunchKernelGGL(small_finish_kernel, dim3(1), dim3(SM_WAVES * 64), 0, s, g.K, f);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the winner's best responses: its row (left in best_x by the fold) through the evaluation
+    // form of the sweep kernel; with no winner the row is whatever the buffer holds and the
+    // responses are not reported
+    SweepArgs ev{};
+    ev.X = f.best_x; ev.count = 1; ev.br_out = f.win_br;
+    small_kernel_t k = small_kernel_for(g.K, true);
+    if (!k) return hipErrorNotSupported;
+    hipLaunchKernelGGL(k, dim3(1), dim3(SM_WAVES * 64), 0, s, g, ev);
     return hipGetLastError();
 }
 
@@ -525,44 +542,43 @@ static inline float bf16_bits_to_float(unsigned short b)
 }
 
 // Host packing for the small-game kernel.
-// Bpack: [tile][instruction i][lane][8] bf16; lane = 32*kh + r supplies, for tile row r = 8q +
-// 4hh + rr (type t = 4*tile + 2*hh + q/2, action j = 4*(q%2) + rr), element e: the part of
-// B_t[k = 4*kh + e%4][j] that instruction i multiplies in that slot: (b1, b1), (b2, b2), (b1, b3)
-// for (e < 4, e >= 4) and i = 0, 1, 2, where b = b1 + b2 + b3 in bf16 parts.
-// ATpack: [type][action][12] fp32: the leader column of (type, action) over the m leader
-// actions, zero padded to 8, then 4 floats of padding.
+// Bpack and ATpack: [tile][instruction i][lane][8] bf16, follower and leader payoffs alike; lane =
+// 32*kh + r supplies, for tile row r = 8q + 4hh + rr (type t = 4*tile + 2*hh + q/2, action
+// j = 4*(q%2) + rr), element e: the part of P_t[k = 4*kh + e%4][j] that instruction i multiplies
+// in that slot: (p1, p1), (p2, p2), (p1, p3) for (e < 4, e >= 4) and i = 0, 1, 2, where
+// P = p1 + p2 + p3 in bf16 parts.
 void small_pack(int m, int n, int K, const float *A, const float *B, void **Bpack, size_t *Bbytes,
                 void **ATpack, size_t *ATbytes)
 {
     const int tiles = K / 4;
     *Bbytes = (size_t)tiles * 3 * 64 * 8 * sizeof(unsigned short);
-    *ATbytes = (size_t)K * SM_N * SM_AT_STRIDE * sizeof(float);
+    *ATbytes = *Bbytes;
     unsigned short *pb = (unsigned short *)calloc(*Bbytes, 1);
-    float *pa = (float *)calloc(*ATbytes, 1);
+    unsigned short *pa = (unsigned short *)calloc(*ATbytes, 1);
     *Bpack = pb; *ATpack = pa;
     if (!pb || !pa) { free(pb); free(pa); *Bpack = nullptr; *ATpack = nullptr; return; }
     static const int part_of[3][2] = { { 0, 0 }, { 1, 1 }, { 0, 2 } };
-    for (int T = 0; T < tiles; ++T)
-        for (int lane = 0; lane < 64; ++lane) {
-            const int kh = lane / 32, r = lane % 32;
-            const int q = r / 8, hh = (r % 8) / 4, rr = r % 4;
-            const int t = 4 * T + 2 * hh + q / 2, j = 4 * (q % 2) + rr;
-            for (int e = 0; e < 8; ++e) {
-                const int k = 4 * kh + e % 4;
-                const float b = k < m ? B[((size_t)t * m + k) * n + j] : 0.0f;
-                unsigned short part[3];
-                part[0] = bf16_rne_bits(b);
-                const float r1 = b - bf16_bits_to_float(part[0]);
-                part[1] = bf16_rne_bits(r1);
-                part[2] = bf16_rne_bits(r1 - bf16_bits_to_float(part[1]));
-                for (int i = 0; i < 3; ++i)
-                    pb[(((size_t)T * 3 + i) * 64 + lane) * 8 + e] = part[part_of[i][e / 4]];
+    for (int which = 0; which < 2; ++which) {
+        const float *P = which ? A : B;
+        unsigned short *out = which ? pa : pb;
+        for (int T = 0; T < tiles; ++T)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int kh = lane / 32, r = lane % 32;
+                const int q = r / 8, hh = (r % 8) / 4, rr = r % 4;
+                const int t = 4 * T + 2 * hh + q / 2, j = 4 * (q % 2) + rr;
+                for (int e = 0; e < 8; ++e) {
+                    const int k = 4 * kh + e % 4;
+                    const float v = k < m ? P[((size_t)t * m + k) * n + j] : 0.0f;
+                    unsigned short part[3];
+                    part[0] = bf16_rne_bits(v);
+                    const float r1 = v - bf16_bits_to_float(part[0]);
+                    part[1] = bf16_rne_bits(r1);
+                    part[2] = bf16_rne_bits(r1 - bf16_bits_to_float(part[1]));
+                    for (int i = 0; i < 3; ++i)
+                        out[(((size_t)T * 3 + i) * 64 + lane) * 8 + e] = part[part_of[i][e / 4]];
+                }
             }
-        }
-    for (int t = 0; t < K; ++t)
-        for (int j = 0; j < n; ++j)
-            for (int i = 0; i < m; ++i)
-                pa[((size_t)t * SM_N + j) * SM_AT_STRIDE + i] = A[((size_t)t * m + i) * n + j];
+    }
 }
 
 }  // namespace bsse
