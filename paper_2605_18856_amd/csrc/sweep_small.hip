@@ -387,7 +387,7 @@ __device__ __forceinline__ void small_body(const GameView &g, const SweepArgs &a
 }
 
 template <int TILES, bool EVAL>
-__global__ void __launch_bounds__(SM_WAVES * 64, 3)
+__global__ void __launch_bounds__(SM_WAVES * 64, TILES == 1 ? 4 : 3)
 sweep_small_kernel(GameView g, SweepArgs a)
 {
     small_body<TILES, EVAL, false>(g, a, blockIdx.x, gridDim.x);
