@@ -37,7 +37,7 @@ EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0}
 # so it is scaled by 2.0; WRITE_SIZE reads a known-size fill exactly).  Keyed by workload; one
 # launch = one chunk.
 TRAFFIC_BYTES = {
-    "config2": (144.5 * 2.0 + 28.9) * 1024.0,          # rows generated in registers: slots and payoffs only
+    "config2": (155.9 * 2.0 + 29.0) * 1024.0,          # rows generated in registers: slots and payoffs only
     "config3": (1068800.0 * 2.0 + 2057.3) * 1024.0,
     "config4": (673309.0 * 2.0 + 270.1) * 1024.0,
     "config5": (3970660.0 * 2.0 + 297.3) * 1024.0,
@@ -288,6 +288,8 @@ def hbm_leg():
             "evals_per_s": count * game.K / (k_ms * 1e-3), "bound": "hbm", "achieved": gbs,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
             "algorithmic_bytes_per_launch": count * 4.0 * game.m,
+            # rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE of this launch (profiles/sweep_kernels_hbm_traffic.md)
+            "traffic": (1048810.0 * 2.0 + 11.4) * 1024.0,
             "best_index": out.best_index,
             "rows_generated_in_the_kernel": {"kernel_ms": ms_gen / k_gen,
                                              "evals_per_s": count * game.K / (ms_gen / k_gen * 1e-3),
@@ -385,6 +387,9 @@ def main():
     ap.add_argument("--only", action="store_true",
                     help="time the named workload only (skip the short extra legs on the other "
                          "configurations and the memory-bound leg)")
+    ap.add_argument("--memory-leg", action="store_true",
+                    help="with --only: still run the memory-bound leg (the small-game sweep kernel over "
+                         "2^26 rows read from a 2 GiB buffer)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (a known-size reference "
                          "kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -458,6 +463,8 @@ def main():
         line["memory_bound_leg"] = hbm_leg()
         line["prior_batch"] = prior_batch_leg()
         line["refinement"] = refinement_leg()
+    elif args.memory_leg:
+        line["memory_bound_leg"] = hbm_leg()
     print(json.dumps(line), flush=True)
 
 
