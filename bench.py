@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0
 PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "valu": 78.6, "valu_bf16": 78.6,
                # fp32 operands split into bf16 parts run on the bf16 matrix cores: priced against
                # that peak with ALGORITHMIC flops (the kernel executes 3x / 6x as many)
-               "mfma_split3": 2500.0, "mfma_split6": 2500.0}
-EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0}
+               "mfma_split3": 2500.0, "mfma_split6": 2500.0, "mfma_small_split6": 2500.0}
+EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0, "mfma_small_split6": 6.0}
 
 # HBM bytes per launch of the fused sweep kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # (profiles/sweep_kernels_hbm_traffic.md; FETCH_SIZE reads half of a known-size copy on this part,

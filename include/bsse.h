@@ -80,7 +80,10 @@ typedef struct {
                     omitted products are below 2^-24 of the terms, so the result is within
                     fp32 rounding of the fp32 dot product.  AUTO picks, in this order, the
                     small-game kernel, MFMA_SPLIT, MFMA, VALU, by what the shape supports.
-                    A forced path on an unsupported shape is BSSE_EINVAL. */
+                    Games with m = n = 8 and K in {4, 8, 12, 16} (fp32 storage) run on the
+                    small-game kernel under AUTO and MFMA alike: bf16 matrix cores on split
+                    operands as under MFMA_SPLIT, at fp32 accuracy (bsse_path_name says
+                    "mfma_small_split6").  A forced path on an unsupported shape is BSSE_EINVAL. */
     int device;  /* HIP device ordinal; -1 = the calling thread's current device */
 } bsse_options;
 

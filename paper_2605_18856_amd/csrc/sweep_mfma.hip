@@ -235,15 +235,17 @@ template <int MP> struct Path<__bf16, MP> {
 struct Geometry {
     int tile_bytes, tpg, types, ts, ats, at_bytes, rec_bytes;
 };
+// terms == 6 (both operands split into bf16 parts) with leader rows in LDS: the leader rows are kept
+// as plain fp32 (mp / terms values and 16 bytes of padding per action), not as parts.
 __host__ __device__ constexpr Geometry make_geometry(int esz, int mp, int n, int stage_tiles,
-                                                     int waves, bool at_lds)
+                                                     int waves, bool at_lds, int terms = 1)
 {
     Geometry q{};
     q.tile_bytes = 32 * mp * esz;
     q.tpg = n >= 32 ? n / 32 : 1;
     q.types = n >= 32 ? 1 : 32 / n;
     q.ts = stage_tiles >= q.tpg ? (stage_tiles / q.tpg) * q.types : 0;     // whole types per stage
-    q.ats = mp + 16 / esz;
+    q.ats = (terms == 6 && at_lds) ? (mp / terms + 4) * 4 / esz : mp + 16 / esz;   // in elements of esz
     q.at_bytes = at_lds ? q.ts * n * q.ats * esz : 0;
     const int unit = waves * 1024;
     q.rec_bytes = (stage_tiles * q.tile_bytes + q.at_bytes + unit - 1) / unit * unit;
@@ -297,7 +299,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     typedef typename P::frag frag;
     typedef typename P::xreg xreg;
     constexpr int KS = P::KSTEPS, HALF = P::HALF;
-    constexpr Geometry G = make_geometry((int)sizeof(T), MP, N, STAGE_TILES, WAVES, AT_LDS);
+    constexpr Geometry G = make_geometry((int)sizeof(T), MP, N, STAGE_TILES, WAVES, AT_LDS, TERMS);
     constexpr int TPG = G.tpg, TYPES = G.types;
     static_assert(N == 8 || N == 16 || N % 32 == 0, "unsupported action count");
     static_assert(STAGE_TILES % TPG == 0 || TPG % STAGE_TILES == 0, "stage/group mismatch");
@@ -342,7 +344,24 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     // ---- candidate rows into registers: lane (col, h) keeps its half of the leader actions,
     // x[c][h*HALF_BASE .. (h+1)*HALF_BASE); on the split path each component becomes TERMS
     // bf16 parts, laid out as TERMS blocks of HALF_BASE to match the packed payoffs
-    xreg x[NT][P::XREGS];
+    // Split path: three bf16 parts per component are stored once each (p0, p1, p2 as blocks of
+    // XB registers); the six k-slot blocks (p0,B0) (p0,B1) (p1,B0) (p0,B2) (p1,B1) (p2,B0) of the
+    // packed payoffs pick them in x_mfma.  Where the leader rows are in LDS they are fp32, and
+    // so is the lane's half of the candidate row that meets them (xf).
+    constexpr bool LEAD_F32 = TERMS == 6 && AT_LDS;
+    constexpr int XB = TERMS > 1 ? HALF_BASE / 2 : P::XREGS;            // registers per part
+    constexpr int XS = TERMS > 1 ? 3 * XB : P::XREGS;                   // registers stored per tile
+    constexpr int SPT = KS / TERMS;                                     // k-steps per block
+    auto x_mfma = [](const frag &fr, const xreg *xc, int s, const f32x16 &c) __attribute__((always_inline)) {
+        if constexpr (TERMS == 6) {
+            constexpr int xsel6[6] = { 0, 0, 1, 0, 1, 2 };
+            return P::mfma(fr, xc + xsel6[s / SPT] * XB + 4 * (s % SPT), 0, c);
+        } else {
+            return P::mfma(fr, xc, s, c);
+        }
+    };
+    xreg x[NT][XS];
+    float xf[NT][LEAD_F32 ? HALF_BASE : 1];
     unsigned valid32[NT];                     // bit c set iff candidate c of the tile exists
 #pragma unroll
     for (int ct = 0; ct < NT; ++ct) {
@@ -363,11 +382,8 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         if constexpr (TERMS == 1) {
             P::pack_x(vb, x[ct]);
         } else {
-            // x = p0 + p1 + p2 with bf16 parts (the subtractions are exact in fp32); blocks pair
-            // with payoff parts as (p0,B0) (p0,B1) (p1,B0) (p0,B2) (p1,B1) (p2,B0), or
-            // (p0,B0) (p1,B0) (p2,B0) when the payoffs are bf16 numbers themselves
-            constexpr int xsel6[6] = { 0, 0, 1, 0, 1, 2 };
-            float v[HALF];
+            // x = p0 + p1 + p2 with bf16 parts (the subtractions are exact in fp32)
+            float v[3 * HALF_BASE];
 #pragma unroll
             for (int e = 0; e < HALF_BASE; ++e) {
                 float part[3];
@@ -377,10 +393,15 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 const float r2 = r1 - part[1];
                 part[2] = __uint_as_float(bf16_bits_rne(r2) << 16);
 #pragma unroll
-                for (int term = 0; term < TERMS; ++term)
-                    v[term * HALF_BASE + e] = part[TERMS == 3 ? term : xsel6[term]];
+                for (int q = 0; q < 3; ++q) v[q * HALF_BASE + e] = part[q];
             }
-            P::pack_x(v, x[ct]);
+#pragma unroll
+            for (int e = 0; e < 3 * HALF_BASE; e += 2)
+                x[ct][e / 2] = bf16_bits_rne(v[e]) | (bf16_bits_rne(v[e + 1]) << 16);
+            if constexpr (LEAD_F32) {
+#pragma unroll
+                for (int e = 0; e < HALF_BASE; ++e) xf[ct][e] = vb[e];
+            }
         }
         valid32[ct] = (unsigned)__builtin_amdgcn_ballot_w64(ok);
     }
@@ -402,6 +423,18 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
         if constexpr (TERMS == 3 && !AT_LDS) return P::half_dot_rep3(xc, colp);
         else return P::half_dot(xc, colp);
     };
+    // fp32 leader rows (LEAD_F32): the lane's HALF_BASE components against its half of the row,
+    // two fused multiply-add chains; the same sequence from LDS and from global memory.
+    auto leader_half_f32 = [&](const float *xc, auto row) __attribute__((always_inline)) {
+        float l0 = 0.0f, l1 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < (LEAD_F32 ? HALF_BASE : 0); e += 4) {
+            const f32x4 r = row[e / 4];
+            l0 = fmaf(xc[e], r[0], l0); l1 = fmaf(xc[e + 1], r[1], l1);
+            l0 = fmaf(xc[e + 2], r[2], l0); l1 = fmaf(xc[e + 3], r[3], l1);
+        }
+        return l0 + l1;
+    };
     // Exact routine for one (candidate tile, type): recomputes the type's tiles one at a time
     // from the packed records in global memory (same instruction sequence, hence the same
     // bits), visits the exact maximisers in ascending action order, lets the leader's payoff
@@ -420,7 +453,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) acc1 = P::mfma(afrags[s * 64 + lane], x[ct], s, acc1);
+            for (int s = 0; s < KS; ++s) acc1 = x_mfma(afrags[s * 64 + lane], x[ct], s, acc1);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -434,8 +467,13 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                         const unsigned long long meq = __builtin_amdgcn_ballot_w64(acc1[r] == gmax);
                         const unsigned hit = (unsigned)(hh ? (meq >> 32) : meq) & valid32[ct];
                         if (hit == 0u) continue;                       // wave-uniform
-                        const float l = pair_sum(
-                            leader_half(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T)));
+                        float lh;
+                        if constexpr (LEAD_F32)
+                            lh = leader_half_f32(xf[ct], reinterpret_cast<const f32x4 *>(
+                                     reinterpret_cast<const float *>(ATpack) + ((size_t)t * N + j) * MP_BASE + h * HALF_BASE));
+                        else
+                            lh = leader_half(x[ct], ATt + ((size_t)j * MP + h * HALF) * sizeof(T));
+                        const float l = pair_sum(lh);
                         if ((hit >> col) & 1u) {
                             if (nmatch == 0 || l > lbest) { lbest = l; jbest = j; }
                             ++nmatch;
@@ -470,7 +508,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 for (int ks = 0; ks < KS; ++ks) {
                     const frag af = base[(size_t)tt * TILE_FRAGS + (size_t)ks * 64 + lane];
 #pragma unroll
-                    for (int ct = 0; ct < NT; ++ct) acc[ct][TT0 + tt] = P::mfma(af, x[ct], ks, acc[ct][TT0 + tt]);
+                    for (int ct = 0; ct < NT; ++ct) acc[ct][TT0 + tt] = x_mfma(af, x[ct], ks, acc[ct][TT0 + tt]);
                 }
             return;
         }
@@ -496,7 +534,7 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 constexpr int f = q * C + decltype(ec)::value;
                 constexpr int tt = TT0 + f / KS, ks = f % KS;
 #pragma unroll
-                for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = P::mfma(fb[q & 1][decltype(ec)::value], x[ct], ks, acc[ct][tt]);
+                for (int ct = 0; ct < NT; ++ct) acc[ct][tt] = x_mfma(fb[q & 1][decltype(ec)::value], x[ct], ks, acc[ct][tt]);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -511,7 +549,10 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
             int js = jstar[ct];
             if (clean[ct]) {
                 float part;
-                if constexpr (AT_LDS)
+                if constexpr (LEAD_F32)
+                    part = leader_half_f32(xf[ct], (const __attribute__((address_space(3))) f32x4 *)(
+                               at_lds + (unsigned)(((ti * N + js) * G.ats) * sizeof(T) + h * HALF_BASE * sizeof(float))));
+                else if constexpr (AT_LDS)
                     part = P::half_dot(x[ct], at_lds + (unsigned)(((ti * N + js) * G.ats + h * HALF) * sizeof(T)));
                 else
                     part = leader_half(x[ct], ATpack + (((size_t)t * N + js) * MP + h * HALF) * sizeof(T));
@@ -1103,7 +1144,7 @@ struct Variant {
     { MODE, TERMSv, MPB, Nv, NTv, Wv, STv, ATL,                                                      \
       sweep_mfma_kernel<T, MPB * TERMSv, Nv, NTv, Wv, STv, OCCv, ATL, TERMSv, false, PFv>,           \
       sweep_mfma_kernel<T, MPB * TERMSv, Nv, 1, Wv, STv, 1, ATL, TERMSv, true, PFv>,                 \
-      make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL), NAME, nullptr, 0 }
+      make_geometry((int)sizeof(T), MPB * TERMSv, Nv, STv, Wv, ATL, TERMSv), NAME, nullptr, 0 }
 // A packing that sweep_wide_kernel also takes (one type per stage, leader rows in LDS, NT = 2)
 #define BSSE_VARIANT_WIDE(T, MODE, MPB, Nv, Wv, PFv, NAME)                                           \
     { MODE, 1, MPB, Nv, 2, Wv, Nv / 32, true,                                                        \
@@ -1126,7 +1167,7 @@ const Variant kVariants[] = {
     BSSE_VARIANT_WIDE(__bf16, 1, 64, 128, 8, 4, "mfma_bf16"),
     // bf16 MFMA on fp32 operands split into bf16 parts
     BSSE_VARIANT(__bf16, 2, 6, 16, 16, 2, 4, 2, 2, true, 0, "mfma_split6"),
-    BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 8, 1, 3, true, 0, "mfma_split6"),
+    BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 4, 1, 3, true, 0, "mfma_split6"),
     BSSE_VARIANT(__bf16, 2, 3, 32, 32, 4, 4, 4, 2, true, 0, "mfma_split3"),
     BSSE_VARIANT(__bf16, 2, 6, 32, 64, 2, 4, 2, 2, true, 0, "mfma_split6"),
     BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 1, 2, false, 0, "mfma_split3"),
@@ -1178,7 +1219,7 @@ int mfma_select(int m, int n, int K, int mode, bool exact)
 
 const char *mfma_variant_name(int variant)
 {
-    if (variant == kSmallVariant) return "mfma_f32";
+    if (variant == kSmallVariant) return "mfma_small_split6";
     return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : "";
 }
 
@@ -1262,7 +1303,9 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
 // variant keeps leader rows in LDS, the rows [type slot][action][MP + pad] of the types the
 // stage covers, in the same slot order.  Rows past K*n and actions past m are zero.
 // ATpack = [K][n][MP] leader payoffs in slot order (zero padded), so that a lane's half of a
-// column is contiguous; used by the global gather and by the exact routine.
+// column is contiguous; used by the global gather and by the exact routine.  Six-term variants that
+// keep leader rows in LDS carry them as plain fp32 instead, in the stage records ([type slot]
+// [action][mp_base + 4]) and in ATpack ([K][n][mp_base]).
 void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B, void **Bpack,
                size_t *Bbytes, void **ATpack, size_t *ATbytes, int *m_pad, int *n_pad)
 {
@@ -1285,7 +1328,8 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
     static const int bsel6[6] = { 0, 1, 0, 2, 1, 0 };
     *m_pad = v->mp_base; *n_pad = n;
     *Bbytes = (size_t)nstages * G.rec_bytes;
-    *ATbytes = (size_t)K * n * MP * esz;
+    const bool lead_f32 = v->terms == 6 && v->at_lds;       // leader rows as plain fp32
+    *ATbytes = lead_f32 ? (size_t)K * n * v->mp_base * sizeof(float) : (size_t)K * n * MP * esz;
     unsigned char *pb = (unsigned char *)calloc(*Bbytes, 1);
     unsigned char *pa = (unsigned char *)calloc(*ATbytes, 1);
     if (!pb || !pa) { free(pb); free(pa); return; }
@@ -1326,17 +1370,29 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
             for (int q = 0; q < G.ts; ++q) {
                 const int t = st * G.ts + q;
                 if (t >= K) break;
-                for (int j = 0; j < n; ++j)
+                for (int j = 0; j < n; ++j) {
+                    if (lead_f32) {
+                        float *row = reinterpret_cast<float *>(ab + ((size_t)q * n + j) * G.ats * esz);
+                        for (int i = 0; i < v->mp_base; ++i) row[i] = i < m ? A[((size_t)t * m + i) * n + j] : 0.0f;
+                        continue;
+                    }
                     for (int hh = 0; hh < 2; ++hh)
                         for (int li = 0; li < half; ++li)
                             put(ab, ((size_t)q * n + j) * G.ats + hh * half + li, slot_value(A, t, j, hh, li));
+                }
             }
         }
     for (int t = 0; t < K; ++t)
-        for (int j = 0; j < n; ++j)
+        for (int j = 0; j < n; ++j) {
+            if (lead_f32) {
+                float *row = reinterpret_cast<float *>(pa) + ((size_t)t * n + j) * v->mp_base;
+                for (int i = 0; i < v->mp_base; ++i) row[i] = i < m ? A[((size_t)t * m + i) * n + j] : 0.0f;
+                continue;
+            }
             for (int hh = 0; hh < 2; ++hh)
                 for (int li = 0; li < half; ++li)
                     put(pa, ((size_t)t * n + j) * MP + hh * half + li, slot_value(A, t, j, hh, li));
+        }
     *Bpack = pb; *ATpack = pa;
 }
 

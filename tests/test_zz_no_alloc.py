@@ -30,8 +30,8 @@ def _same(a, b):
 # (m, n, K, payoff kind, storage, expected path prefix)
 GAMES = [
     (3, 3, 2, "normal", "f32", "valu"),
-    (8, 8, 4, "normal", "f32", "mfma_f32"),            # small-game kernel: running-best slots
-    (8, 8, 16, "dup", "f32", "mfma_f32"),
+    (8, 8, 4, "normal", "f32", "mfma_small_split6"),            # small-game kernel: running-best slots
+    (8, 8, 16, "dup", "f32", "mfma_small_split6"),
     (32, 32, 16, "normal", "f32", "mfma_split6"),
     (64, 128, 4, "uniform", "bf16", "mfma_bf16"),
     (128, 256, 2, "int", "f32", "mfma_split3"),
