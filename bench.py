@@ -38,7 +38,7 @@ EXECUTED_FLOP_FACTOR = {"mfma_split3": 3.0, "mfma_split6": 6.0, "mfma_small_spli
 # launch = one chunk.
 TRAFFIC_BYTES = {
     "config2": (155.9 * 2.0 + 29.0) * 1024.0,          # rows generated in registers: slots and payoffs only
-    "config3": (1068800.0 * 2.0 + 2057.3) * 1024.0,
+    "config3": (1050370.0 * 2.0 + 4097.3) * 1024.0,
     "config4": (673309.0 * 2.0 + 270.1) * 1024.0,
     "config5": (3970660.0 * 2.0 + 297.3) * 1024.0,
 }
