@@ -237,11 +237,14 @@ struct Geometry {
 };
 // terms == 6 (both operands split into bf16 parts) with leader rows in LDS: the leader rows are kept
 // as plain fp32 (mp / terms values and 16 bytes of padding per action), not as parts.
+// terms == 3 (payoffs that are bf16 numbers against the three parts of the candidate): the three
+// blocks of a row tile's fragments would be identical, so a tile holds one block (mp / 3 slots)
+// and every fragment read serves three matrix instructions.
 __host__ __device__ constexpr Geometry make_geometry(int esz, int mp, int n, int stage_tiles,
                                                      int waves, bool at_lds, int terms = 1)
 {
     Geometry q{};
-    q.tile_bytes = 32 * mp * esz;
+    q.tile_bytes = 32 * (terms == 3 ? mp / 3 : mp) * esz;
     q.tpg = n >= 32 ? n / 32 : 1;
     q.types = n >= 32 ? 1 : 32 / n;
     q.ts = stage_tiles >= q.tpg ? (stage_tiles / q.tpg) * q.types : 0;     // whole types per stage
@@ -304,7 +307,10 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
     static_assert(N == 8 || N == 16 || N % 32 == 0, "unsupported action count");
     static_assert(STAGE_TILES % TPG == 0 || TPG % STAGE_TILES == 0, "stage/group mismatch");
     static_assert(!AT_LDS || STAGE_TILES >= TPG, "leader rows in LDS need whole types per stage");
-    constexpr int TILE_FRAGS = KS * 64;                 // fragments per row tile
+    constexpr int REP = TERMS == 3 ? 3 : 1;             // matrix instructions per fragment read
+    constexpr int KF = KS / REP;                        // fragment k-steps per row tile
+    constexpr int TILE_FRAGS = KF * 64;                 // fragments per row tile
+    static_assert(PF == 0 || REP == 1, "the chunked fragment read-ahead takes one instruction per fragment");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ float red_v[WAVES];
@@ -453,7 +459,11 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc1[r] = 0.0f;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) acc1 = x_mfma(afrags[s * 64 + lane], x[ct], s, acc1);
+            for (int s = 0; s < KF; ++s) {
+                const frag af = afrags[s * 64 + lane];
+#pragma unroll
+                for (int q = 0; q < REP; ++q) acc1 = x_mfma(af, x[ct], q * KF + s, acc1);
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -505,10 +515,13 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 #pragma unroll
             for (int tt = 0; tt < NTILES; ++tt)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
+                for (int ks = 0; ks < KF; ++ks) {
                     const frag af = base[(size_t)tt * TILE_FRAGS + (size_t)ks * 64 + lane];
 #pragma unroll
-                    for (int ct = 0; ct < NT; ++ct) acc[ct][TT0 + tt] = x_mfma(af, x[ct], ks, acc[ct][TT0 + tt]);
+                    for (int q = 0; q < REP; ++q)
+#pragma unroll
+                        for (int ct = 0; ct < NT; ++ct)
+                            acc[ct][TT0 + tt] = x_mfma(af, x[ct], q * KF + ks, acc[ct][TT0 + tt]);
                 }
             return;
         }
@@ -687,6 +700,15 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
 
     stage_sync();                              // the first stage is in LDS
     const int groups = row_tiles / TPG;
+    // Two roles where the epilogue reads nothing from LDS (leader rows gathered from global memory),
+    // a stage holds whole types and one workgroup fills the compute unit: the late half of the
+    // wavefronts passes the barrier that ends a stage BEFORE the stage's last epilogue, the early half
+    // after it, so that behind every barrier the two wavefronts of a SIMD are one epilogue apart
+    // -- one on the matrix pipe, one on the vector unit -- instead of wanting the same unit at the
+    // same time (measured on the m=128 n=256 three-term variant: 4 %; with a barrier per row tile
+    // the late half held the early half up instead, and on the wide bf16 kernel it gained nothing).
+    constexpr bool ROLES = !AT_LDS && !SLICED && WAVES == 8 && STAGE_TILES >= TPG;
+    const bool late = ROLES && wave >= WAVES / 2;
     if constexpr (STAGE_TILES >= TPG) {
         constexpr int GPS = STAGE_TILES / TPG;                          // groups per stage
 #pragma unroll 1
@@ -701,9 +723,10 @@ sweep_mfma_kernel(GameView g, SweepArgs a, int row_tiles)
                 zero_acc();
                 mfma_run(tiles + (size_t)(gi * TPG) * TILE_FRAGS, std::integral_constant<int, TPG>{},
                          std::integral_constant<int, 0>{});
+                if (ROLES && late && gi == ng - 1) stage_sync();
                 epilogue(g0 + gi, (const lds_byte *)buf + (unsigned)(STAGE_TILES * G.tile_bytes + gi * TYPES * N * G.ats * sizeof(T)));
             }
-            stage_sync();
+            if (!(ROLES && late) || ng <= 0) stage_sync();      // (every wavefront: one barrier per stage)
         }
     } else {
         constexpr int SPG = TPG / STAGE_TILES;                          // stages per group
@@ -1170,7 +1193,7 @@ const Variant kVariants[] = {
     BSSE_VARIANT(__bf16, 2, 6, 32, 32, 2, 4, 1, 3, true, 0, "mfma_split6"),
     BSSE_VARIANT(__bf16, 2, 3, 32, 32, 4, 4, 4, 2, true, 0, "mfma_split3"),
     BSSE_VARIANT(__bf16, 2, 6, 32, 64, 2, 4, 2, 2, true, 0, "mfma_split6"),
-    BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 1, 2, false, 0, "mfma_split3"),
+    BSSE_VARIANT(__bf16, 2, 3, 128, 256, 1, 8, 8, 2, false, 0, "mfma_split3"),
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 constexpr int kSmallVariant = 1000;          // the small-game kernel (sweep_small.hip)
@@ -1296,7 +1319,8 @@ hipError_t launch_sweep_mfma(const GameView &g, const SweepArgs &a, hipStream_t 
 // The contraction index of a variant runs over MP = terms * mp_base slots.  Lane half h owns
 // slots h*MP/2 .. (h+1)*MP/2; within a half, slot = term * mp_base/2 + (i - h*mp_base/2) for the
 // leader actions i of that half, and the value stored at (term, i) is part q(term) of the payoff:
-// the payoff itself when terms == 1, parts (0,1,0,2,1,0) for six terms, (0,0,0) for three.
+// the payoff itself when terms == 1, parts (0,1,0,2,1,0) for six terms, (0,0,0) for three (whose
+// fragments hold the first block only: the kernel uses each for all three terms).
 // Bpack = stage records (see Geometry): per stage, STAGE_TILES row tiles, each laid out as
 // [k-step][lane 0..63][fragment], where lane = 32*h + rowInTile supplies the slots
 // h*MP/2 + (elements per lane)*s + e of (type, action) row 32*tile + rowInTile; then, when the
@@ -1321,7 +1345,7 @@ void mfma_pack(int variant, int m, int n, int K, const float *A, const float *B,
     const int MP = v->mp_base * v->terms, half = MP / 2, half_base = v->mp_base / 2;
     const bool bf = v->mode != 0;
     const int epl = bf ? 8 : 1;                            // k-slots per lane per MFMA
-    const int ks = half / epl;
+    const int ks = half / epl / (v->terms == 3 ? 3 : 1);   // fragment k-steps per tile (one block of three-term rows)
     const int tiles = row_tiles_for(*v, K);
     const int nstages = (tiles + v->stage_tiles - 1) / v->stage_tiles;
     const size_t esz = bf ? 2 : 4;
