@@ -40,7 +40,7 @@ TRAFFIC_BYTES = {
     "config2": (155.9 * 2.0 + 29.0) * 1024.0,          # rows generated in registers: slots and payoffs only
     "config3": (1050370.0 * 2.0 + 4097.3) * 1024.0,
     "config4": (673309.0 * 2.0 + 270.1) * 1024.0,
-    "config5": (3970660.0 * 2.0 + 297.3) * 1024.0,
+    "config5": (1867050.0 * 2.0 + 301.7) * 1024.0,
 }
 
 # workload -> (config number, candidates per step, candidates per chunk (= per launch), note)
