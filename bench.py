@@ -43,6 +43,13 @@ TRAFFIC_BYTES = {
     "config5": (1867050.0 * 2.0 + 301.7) * 1024.0,
 }
 
+# Matrix and vector instructions a wavefront alternates between in the fused sweep kernel of a
+# workload, from the rocprofv3 counters in profiles/ (SQ_INSTS_MFMA and SQ_INSTS_VALU minus it, per
+# wavefront and block of one type, rounded to the measurement's granularity of 24): config 4, one
+# pass of two candidate tiles: 32 and 2 x 156; config 3, two candidate tiles: 24 and 2 x 105;
+# config 5, one tile: 192 and 379.
+MIXES = {"config4": (32, 312), "config3": (24, 216), "config5": (192, 384)}
+
 # workload -> (config number, candidates per step, candidates per chunk (= per launch), note)
 WORKLOADS = {
     "config1": (1, None, None, "m=n=3 K=2 lattice N=100 (5151 candidates)"),
@@ -446,6 +453,14 @@ def main():
         rf = line["roofline"]
         key = {"GB/s": "stream_read_GBs", "TFLOP/s": "mfma_bf16_TFLOPs" if rf["peak"] == 2500.0 else "mfma_f32_TFLOPs"}[rf["unit"]]
         rf["frac_of_measured_ceiling"] = rf["achieved"] / c[key]
+        if args.workload in MIXES:
+            # what the bf16 matrix cores keep under this kernel's mix of matrix and vector instructions
+            # with nothing else in the way (no loads, dependencies or barriers)
+            nm, nv = MIXES[args.workload]
+            mix = bsse.bsse_mixed_ceiling(nm, nv) / EXECUTED_FLOP_FACTOR.get(r["path"], 1.0)
+            c["mfma_bf16_TFLOPs_under_this_kernels_instruction_mix"] = mix
+            c["instruction_mix"] = {"mfma_per_block": nm, "vector_per_block": nv}
+            rf["frac_of_mixed_ceiling"] = rf["achieved"] / mix
     if not args.only:
         # short extra legs: the other configurations (not part of `value`), and the sweep
         # kernel alone on a batch far larger than the caches for the memory-bound game

@@ -335,6 +335,17 @@ bsse_status bsse_get_timing(bsse_game *g, double *kernel_ms_out, int64_t *launch
 bsse_status bsse_measure_ceilings(int device, double *stream_read_gbs, double *mfma_bf16_tflops,
                                   double *mfma_f32_tflops, double *empty_launch_us);
 
+/* One more measured ceiling (diagnostics; no part of the sweep): the rate the bf16 matrix cores
+ * keep, in TFLOP/s of 32x32x16 instructions, when every wavefront alternates blocks of
+ * mfma_per_round matrix instructions (a multiple of 4, at most 4096) with blocks of valu_per_round
+ * independent vector instructions (a multiple of 24, at most 65536: three-operand maxima, compares
+ * into scalar masks and selects under them in equal parts), two wavefronts per SIMD on every
+ * compute unit, nothing loaded or stored.  With the counts of a sweep kernel's instruction mix it
+ * says what that mix could reach without loads, dependencies and barriers.  device = HIP ordinal,
+ * -1 = current; uses the null stream and waits for it; the output is a host pointer. */
+bsse_status bsse_measure_mixed_ceiling(int device, int mfma_per_round, int valu_per_round,
+                                       double *mfma_bf16_tflops);
+
 const char *bsse_last_error(void); /* thread-local; "" if none */
 const char *bsse_status_name(bsse_status s);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "bsse_profile_lp", "bsse_polish", "bsse_sweep_topk", "bsse_lattice_around",
     "bsse_dirichlet_around", "bsse_refine", "bsse_solve_realised", "bsse_sweep_dirichlet",
     "bsse_sweep_dirichlet_chunk", "bsse_sweep_best_row", "bsse_measure_ceilings",
+    "bsse_measure_mixed_ceiling",
     "bsse_sweep_static",
 ]
 
@@ -99,6 +100,7 @@ def lib():
     L.bsse_get_timing.argtypes = [vp, P(ctypes.c_double), P(i64)]
     L.bsse_measure_ceilings.argtypes = [i32, P(ctypes.c_double), P(ctypes.c_double), P(ctypes.c_double),
                                         P(ctypes.c_double)]
+    L.bsse_measure_mixed_ceiling.argtypes = [i32, i32, i32, P(ctypes.c_double)]
     L.bsse_last_error.argtypes = []
     L.bsse_last_error.restype = ctypes.c_char_p
     L.bsse_status_name.argtypes = [i32]
@@ -473,3 +475,13 @@ def bsse_ceilings(device: int = -1) -> dict:
         raise BsseError(st, "bsse_measure_ceilings failed")
     return {"stream_read_GBs": d[0].value, "mfma_bf16_TFLOPs": d[1].value,
             "mfma_f32_TFLOPs": d[2].value, "empty_launch_us": d[3].value}
+
+
+def bsse_mixed_ceiling(mfma_per_round: int, valu_per_round: int, device: int = -1) -> float:
+    """bf16 matrix-core TFLOP/s under a given mix of matrix and vector instructions (see
+    bsse_measure_mixed_ceiling)."""
+    d = ctypes.c_double()
+    st = lib().bsse_measure_mixed_ceiling(int(device), int(mfma_per_round), int(valu_per_round), ctypes.byref(d))
+    if st != BSSE_OK:
+        raise BsseError(st, "bsse_measure_mixed_ceiling failed")
+    return d.value

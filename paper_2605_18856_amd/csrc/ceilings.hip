@@ -1,7 +1,10 @@
 // What this device reaches on plain kernels, measured beside the vendor peaks the roofline
 // fractions are quoted against: a streaming read of a buffer far larger than the caches, a loop
 // of independent matrix-core instructions (bf16 32x32x16 and fp32 32x32x2), and the latency of
-// an empty launch.  Diagnostics only: nothing of the sweep runs here.
+// an empty launch; and the rate the bf16 matrix cores keep when a wavefront's matrix instructions
+// alternate with blocks of independent vector instructions (the instruction mix of a sweep kernel
+// with its loads, dependencies and barriers taken away).  Diagnostics only: nothing of the sweep
+// runs here.
 #include "../../include/bsse.h"
 #include <hip/hip_runtime.h>
 #include <chrono>
@@ -64,6 +67,71 @@ mfma_loop_kernel(int iters, float *__restrict__ sink)
 }
 
 __global__ void empty_kernel() {}
+
+// Rounds of `mfma_groups` x 4 matrix instructions (four independent accumulators) followed by
+// `valu_groups` x 24 vector instructions of the kinds an arg-max epilogue is made of (three-operand
+// maximum, compare into a scalar mask, select under a scalar mask, in equal parts, two
+// independent chains), eight wavefronts per workgroup and one workgroup per compute unit (the
+// dynamic LDS the launch asks for keeps a second one away): two wavefronts per SIMD, each with
+// the other's vector block to run beside its matrix block.  Nothing is loaded or stored.
+#define BSSE_MIX6                                                                             \
+    "v_max3_f32 %[v0], %[v0], %[c0], %[c1]\n\t"                                               \
+    "v_max3_f32 %[v1], %[v1], %[c1], %[c0]\n\t"                                               \
+    "v_cmp_eq_f32 %[m0], %[v0], %[c0]\n\t"                                                    \
+    "v_cmp_eq_f32 %[m1], %[v1], %[c0]\n\t"                                                    \
+    "s_nop 0\n\t"                                                                             \
+    "v_cndmask_b32 %[w0], %[w0], %[c1], %[m0]\n\t"                                            \
+    "v_cndmask_b32 %[w1], %[w1], %[c0], %[m1]\n\t"
+__global__ void __launch_bounds__(512, 2)
+mixed_loop_kernel(int rounds, int mfma_groups, int valu_groups, float *__restrict__ sink)
+{
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[q][r] = 0.0f;
+    const float seed = (float)(threadIdx.x & 7) * 0.125f;
+    bf16x8 ab, bb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ab[e] = (__bf16)(seed + (float)e); bb[e] = (__bf16)(1.0f - seed); }
+    float v0 = seed, v1 = seed + 1.0f, w0 = 0.0f, w1 = 0.0f;
+    const float c0 = 0.5f + seed, c1 = 0.25f;
+    // (long trips first, the remainder in short ones: the loop overhead of a short trip is a few
+    // per cent of its instructions' issue time)
+    auto mfma4 = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ab, bb, acc[q], 0, 0, 0);
+    };
+    auto valu24 = [&]() __attribute__((always_inline)) {
+        unsigned long long m0, m1;
+        asm volatile(BSSE_MIX6 BSSE_MIX6 BSSE_MIX6 BSSE_MIX6
+                     : [v0] "+v"(v0), [v1] "+v"(v1), [w0] "+v"(w0), [w1] "+v"(w1), [m0] "=&s"(m0), [m1] "=&s"(m1)
+                     : [c0] "v"(c0), [c1] "v"(c1));
+    };
+#pragma unroll 1
+    for (int it = 0; it < rounds; ++it) {
+#pragma unroll 1
+        for (int g = 0; g < (mfma_groups >> 3); ++g) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mfma4();
+        }
+#pragma unroll 1
+        for (int g = 0; g < (mfma_groups & 7); ++g) mfma4();
+#pragma unroll 1
+        for (int g = 0; g < (valu_groups >> 2); ++g) {
+            valu24(); valu24(); valu24(); valu24();
+        }
+#pragma unroll 1
+        for (int g = 0; g < (valu_groups & 3); ++g) valu24();
+    }
+    float s = v0 + v1 + w0 + w1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[q][r];
+    if (s == -1.2345e30f) *sink = s;
+}
 
 struct Ev {
     hipEvent_t a = nullptr, b = nullptr;
@@ -162,6 +230,64 @@ extern "C" bsse_status bsse_measure_ceilings(int device, double *stream_read_gbs
     *empty_launch_us = std::chrono::duration<double, std::micro>(t1 - t0).count() / n;
     *stream_read_gbs = read_gbs; *mfma_bf16_tflops = tf[0]; *mfma_f32_tflops = tf[1];
 
+    (void)hipFree(sink);
+    if (prev >= 0) (void)hipSetDevice(prev);
+    return BSSE_OK;
+}
+
+#define MIX_TRY(call)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            if (sink) (void)hipFree(sink);                                                    \
+            if (prev >= 0) (void)hipSetDevice(prev);                                          \
+            return e_ == hipErrorOutOfMemory ? BSSE_ENOMEM : BSSE_EDEVICE;                    \
+        }                                                                                     \
+    } while (0)
+
+extern "C" bsse_status bsse_measure_mixed_ceiling(int device, int mfma_per_round, int valu_per_round,
+                                                  double *mfma_bf16_tflops)
+{
+    if (!mfma_bf16_tflops || device < -1) return BSSE_EINVAL;
+    if (mfma_per_round < 4 || mfma_per_round > 4096 || mfma_per_round % 4 != 0) return BSSE_EINVAL;
+    if (valu_per_round < 0 || valu_per_round > 65536 || valu_per_round % 24 != 0) return BSSE_EINVAL;
+    float *sink = nullptr;
+    int prev = -1;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return BSSE_EDEVICE;
+    if (device >= ndev) return BSSE_EINVAL;
+    if (device >= 0) {
+        int cur = -1;
+        if (hipGetDevice(&cur) != hipSuccess) return BSSE_EDEVICE;
+        if (cur != device) { prev = cur; if (hipSetDevice(device) != hipSuccess) return BSSE_EDEVICE; }
+    }
+    int dev = device;
+    if (dev < 0) MIX_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    MIX_TRY(hipGetDeviceProperties(&prop, dev));
+    const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    Ev ev;
+    MIX_TRY(hipEventCreate(&ev.a));
+    MIX_TRY(hipEventCreate(&ev.b));
+    MIX_TRY(hipMalloc((void **)&sink, 256));
+    const int lds = 96 * 1024;                 // more than half of a compute unit's LDS: one workgroup each
+    MIX_TRY(hipFuncSetAttribute((const void *)mixed_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    // about 2e5 matrix instructions per wavefront: tens of milliseconds
+    const int rounds = 200000 / mfma_per_round > 0 ? 200000 / mfma_per_round : 1;
+    double best = 1e30;
+    for (int rep = 0; rep < 4; ++rep) {
+        MIX_TRY(hipEventRecord(ev.a, nullptr));
+        hipLaunchKernelGGL(mixed_loop_kernel, dim3((unsigned)cus), dim3(512), (size_t)lds, nullptr, rounds,
+                           mfma_per_round / 4, valu_per_round / 24, sink);
+        MIX_TRY(hipGetLastError());
+        MIX_TRY(hipEventRecord(ev.b, nullptr));
+        MIX_TRY(hipEventSynchronize(ev.b));
+        float ms = 0.0f;
+        MIX_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
+        if (rep > 0 && ms < best) best = ms;
+    }
+    const double total = (double)cus * 8.0 * rounds * mfma_per_round * (2.0 * 32 * 32 * 16);
+    *mfma_bf16_tflops = total / (best * 1e-3) / 1e12;
     (void)hipFree(sink);
     if (prev >= 0) (void)hipSetDevice(prev);
     return BSSE_OK;

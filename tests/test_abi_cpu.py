@@ -104,6 +104,17 @@ def test_null_handles_are_rejected():
     assert bsse.lib().bsse_path_name(None) == b""
 
 
+def test_ceiling_measurements_check_their_arguments_first():
+    L = bsse.lib()
+    d = ctypes.c_double()
+    assert L.bsse_measure_ceilings(-1, None, None, None, None) == bsse.BSSE_EINVAL
+    assert L.bsse_measure_ceilings(-2, ctypes.byref(d), ctypes.byref(d), ctypes.byref(d), ctypes.byref(d)) == bsse.BSSE_EINVAL
+    assert L.bsse_measure_mixed_ceiling(-1, 32, 312, None) == bsse.BSSE_EINVAL
+    assert L.bsse_measure_mixed_ceiling(-2, 32, 312, ctypes.byref(d)) == bsse.BSSE_EINVAL
+    for mf, va in [(0, 24), (3, 24), (4100, 24), (32, -24), (32, 30), (32, 65544)]:
+        assert L.bsse_measure_mixed_ceiling(-1, mf, va, ctypes.byref(d)) == bsse.BSSE_EINVAL
+
+
 def test_lattice_count_on_host():
     from math import comb
     for m, N in [(3, 100), (1, 9), (2, 1), (8, 12), (32, 6), (4, 1000)]:
