@@ -45,9 +45,9 @@ def pytest_terminal_summary(terminalreporter, exitstatus, config):
         "%d of %d sweeps" % (len(ev), tot["n_evals"], tot["br_mismatch"], tot["flagged"],
                               tot["bound_explained"], tot["hard"],
                               sum(r["same_index"] for r in wn), len(wn)))
-    out = os.path.join(ROOT, "gpurun_out")
-    if os.path.isdir(out):
+    out = os.environ.get("BSSE_PARITY_LOG")          # a file to keep the counts in, if asked for
+    if out:
         import json
-        with open(os.path.join(out, "parity_counts.json"), "w") as f:
+        with open(out, "w") as f:
             json.dump({"totals": tot, "winner_checks": len(wn),
                        "winner_same_index": sum(r["same_index"] for r in wn), "log": parity.LOG}, f)
