@@ -401,9 +401,12 @@ def main():
                     help="also run a plain 256 MiB device copy 5 times (a known-size reference "
                          "kernel for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--ceilings", action="store_true",
-                    help="also measure what this box reaches on plain kernels (stream read GB/s, "
-                         "bf16 and fp32 MFMA loop TFLOP/s, empty-launch latency) and report the "
-                         "fractions against them beside those against the vendor peaks")
+                    help="(the default unless --only is given) also measure what this box reaches on "
+                         "plain kernels (stream read GB/s, bf16 and fp32 MFMA loop TFLOP/s, empty-launch "
+                         "latency, MFMAs under the sweep kernel's own mix of matrix and vector "
+                         "instructions) and report the fractions against them beside those against the "
+                         "vendor peaks; a few seconds, outside every timed region")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured ceilings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -446,7 +449,7 @@ def main():
         "result": {"best_index": r["best_index"], "best_value": r["best_value"],
                    "n_tie_evals": r["n_tie_evals"]},
     }
-    if args.ceilings:
+    if (args.ceilings or not args.only) and not args.no_ceilings:
         from paper_2605_18856_amd import bsse
         c = bsse.bsse_ceilings()
         line["measured_ceilings"] = c
