@@ -477,6 +477,13 @@ def main():
                          "candidates_per_step": o["count"], "candidates_per_launch": o["chunk"],
                          "roofline": {k: o["roofline"][k] for k in
                                       ("bound", "achieved", "peak", "unit", "frac", "kernel_ms", "traffic")}}
+            if w in MIXES and not args.no_ceilings:
+                from paper_2605_18856_amd import bsse
+                nm, nv = MIXES[w]
+                mix = bsse.bsse_mixed_ceiling(nm, nv) / EXECUTED_FLOP_FACTOR.get(o["path"], 1.0)
+                others[w]["roofline"]["mixed_ceiling"] = mix
+                others[w]["roofline"]["instruction_mix"] = {"mfma_per_block": nm, "vector_per_block": nv}
+                others[w]["roofline"]["frac_of_mixed_ceiling"] = o["roofline"]["achieved"] / mix
         line["other_workloads"] = others
         line["memory_bound_leg"] = hbm_leg()
         line["prior_batch"] = prior_batch_leg()
